@@ -1,0 +1,114 @@
+"""Constructive reference for the workgroup-ID -> output-tile map (test infrastructure only).
+
+What is modelled (SwizzlePerf, Introduction and Appendix "Case Study: GEMM Swizzling"):
+the hardware hands workgroup ``w`` of a 1-D launch to XCD ``w mod X`` (round-robin), and the
+swizzle renumbers workgroups so that each XCD ends up owning one contiguous run of logical
+tile ids ("all contiguous blocks on the same XCD before moving to the next XCD").
+
+The paper's printed closed form only covers launches whose size is a multiple of X, so this
+oracle does not use a formula at all: it literally deals the workgroups to the XCDs and then
+numbers them XCD by XCD.  The grouped-M raster (not in the paper; a band of ``group_m`` tile
+rows is walked column by column before the next band starts) is likewise built as an explicit
+list.  No closed form of the library appears in this file.
+
+Modes: 0 = identity + row-major, 1 = XCD renumbering + row-major,
+       2 = XCD renumbering + grouped-M, 3 = identity + grouped-M.
+"""
+from __future__ import annotations
+
+MODE_RR, MODE_XCD, MODE_XCD_GROUPM, MODE_GROUPM = 0, 1, 2, 3
+
+
+def deal_round_robin(num_wg: int, num_xcd: int) -> list[list[int]]:
+    """Hardware dispatch: bucket[x] lists, in launch order, the workgroups that XCD x receives."""
+    buckets: list[list[int]] = [[] for _ in range(num_xcd)]
+    for w in range(num_wg):
+        buckets[w % num_xcd].append(w)
+    return buckets
+
+
+def logical_ids(num_wg: int, num_xcd: int, xcd_remap: bool) -> list[int]:
+    """l[w]: the logical id workgroup w works on."""
+    if not xcd_remap:
+        return list(range(num_wg))
+    l_of_w = [-1] * num_wg
+    nxt = 0
+    for bucket in deal_round_robin(num_wg, num_xcd):   # XCD 0 first, then XCD 1, ...
+        for w in bucket:                               # inside an XCD: dispatch order
+            l_of_w[w] = nxt
+            nxt += 1
+    return l_of_w
+
+
+def raster_order(grid_m: int, grid_n: int, group_m: int, grouped: bool) -> list[tuple[int, int]]:
+    """order[l] = (pm, pn): the tile visited l-th."""
+    order: list[tuple[int, int]] = []
+    if not grouped:
+        for pm in range(grid_m):
+            for pn in range(grid_n):
+                order.append((pm, pn))
+        return order
+    first = 0
+    while first < grid_m:
+        rows_in_band = min(group_m, grid_m - first)     # the last band may be shorter
+        for pn in range(grid_n):
+            for pm in range(first, first + rows_in_band):
+                order.append((pm, pn))
+        first += group_m
+    return order
+
+
+def pid_map(grid_m: int, grid_n: int, num_xcd: int, group_m: int, mode: int) -> list[int]:
+    """out[w] = pm * grid_n + pn, the output tile that hardware workgroup w computes."""
+    if grid_m < 1 or grid_n < 1 or num_xcd < 1 or group_m < 1 or mode not in (0, 1, 2, 3):
+        raise ValueError("bad arguments")
+    num_wg = grid_m * grid_n
+    l_of_w = logical_ids(num_wg, num_xcd, xcd_remap=mode in (MODE_XCD, MODE_XCD_GROUPM))
+    order = raster_order(grid_m, grid_n, group_m, grouped=mode in (MODE_XCD_GROUPM, MODE_GROUPM))
+    out = []
+    for w in range(num_wg):
+        pm, pn = order[l_of_w[w]]
+        out.append(pm * grid_n + pn)
+    return out
+
+
+# ----------------------------------------------------------------------------------------
+# Invariant checkers: they judge ANY candidate map (the oracle's, the library's, a broken one).
+# ----------------------------------------------------------------------------------------
+
+def is_permutation(out, num_wg: int) -> bool:
+    """True iff out is a bijection onto [0, num_wg) (the paper's pass/fail criterion for a remap)."""
+    if len(out) != num_wg:
+        return False
+    seen = [False] * num_wg
+    for t in out:
+        t = int(t)
+        if t < 0 or t >= num_wg or seen[t]:
+            return False
+        seen[t] = True
+    return True
+
+
+def xcd_tile_sets(out, num_xcd: int) -> list[list[int]]:
+    """Tiles each XCD computes, in its dispatch order, under round-robin dispatch."""
+    return [[int(out[w]) for w in bucket] for bucket in deal_round_robin(len(out), num_xcd)]
+
+
+def fair_share(out, num_xcd: int) -> bool:
+    """XCD x computes floor(T/X) tiles, plus one if x < T mod X."""
+    t = len(out)
+    return all(len(s) == t // num_xcd + (1 if x < t % num_xcd else 0)
+               for x, s in enumerate(xcd_tile_sets(out, num_xcd)))
+
+
+def xcd_runs_contiguous(out, grid_m: int, grid_n: int, group_m: int, grouped: bool, num_xcd: int) -> bool:
+    """Each XCD's tiles are one contiguous, increasing run of the raster order, runs abutting in XCD order."""
+    order = raster_order(grid_m, grid_n, group_m, grouped)
+    pos = {pm * grid_n + pn: l for l, (pm, pn) in enumerate(order)}
+    expect = 0
+    for tiles in xcd_tile_sets(out, num_xcd):
+        for t in tiles:
+            if pos[t] != expect:
+                return False
+            expect += 1
+    return expect == len(out)

@@ -1,0 +1,121 @@
+"""Pins for the constructive PID-map oracle: each checks it against something other than itself."""
+import itertools
+import os
+
+import pytest
+
+from oracle import pid_map as opm
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def paper_printed_swizzle(pid, num_blocks, num_xcds):
+    # The closed form printed in the paper's GEMM appendix figure (ceil-divided blocks per XCD).
+    b_per_xcd = (num_blocks + num_xcds - 1) // num_xcds
+    return (pid % num_xcds) * b_per_xcd + pid // num_xcds
+
+
+def test_worked_example_4x5_on_4_xcds():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "gemm_swizzle_4x5_xcd4.txt")) if not l.startswith("#")]
+    want = [int(t) for _, t in rows]
+    assert [int(w) for w, _ in rows] == list(range(20))
+    assert opm.pid_map(4, 5, 4, 1, opm.MODE_XCD) == want
+    # the point of the example: every XCD owns one whole tile-row of C (shares A's row panel)
+    for x, tiles in enumerate(opm.xcd_tile_sets(want, 4)):
+        assert {t // 5 for t in tiles} == {x}
+
+
+@pytest.mark.parametrize("num_blocks,num_xcds", [(304, 8), (256, 8), (1024, 8), (512, 8), (1120, 8), (20, 4),
+                                                 (16, 8), (96, 12), (7, 7), (35, 5)])
+def test_equals_paper_formula_when_divisible(num_blocks, num_xcds):
+    assert num_blocks % num_xcds == 0
+    want = [paper_printed_swizzle(w, num_blocks, num_xcds) for w in range(num_blocks)]
+    assert opm.logical_ids(num_blocks, num_xcds, True) == want
+
+
+def test_paper_formula_is_not_a_bijection_on_ragged_counts_and_checker_says_so():
+    bad = [paper_printed_swizzle(w, 10, 8) for w in range(10)]
+    assert bad == [0, 2, 4, 6, 8, 10, 12, 14, 1, 3]
+    assert not opm.is_permutation(bad, 10)
+    # ... whereas the dealt-and-numbered map is
+    assert opm.is_permutation(opm.logical_ids(10, 8, True), 10)
+
+
+def test_checker_rejects_bit_swap_remap_on_non_power_of_two():
+    # the "hardware-overload" pattern printed in the paper's bitwise-swizzling appendix
+    def swap(pid):
+        return ((pid >> 1) & 0x55555555) | ((pid & 0x55555555) << 1)
+    assert opm.is_permutation([swap(p) for p in range(16)], 16)       # fine on 16
+    assert not opm.is_permutation([swap(p) for p in range(21)], 21)   # sends 20 -> 24
+    assert not opm.is_permutation([0, 1, 1, 3], 4)
+    assert not opm.is_permutation([0, 1, 2], 4)
+    assert not opm.is_permutation([0, 1, 2, -1], 4)
+
+
+@pytest.mark.parametrize("T,X", [(t, x) for t in range(1, 70) for x in range(1, 13)])
+def test_xcd_numbering_is_the_rank_under_sorting_by_xcd_then_launch_order(T, X):
+    # Independent route: sort the workgroups by (XCD they land on, launch order); rank = logical id.
+    by_xcd = sorted(range(T), key=lambda w: (w % X, w))
+    want = [0] * T
+    for rank, w in enumerate(by_xcd):
+        want[w] = rank
+    assert opm.logical_ids(T, X, True) == want
+
+
+@pytest.mark.parametrize("gm,gn,g", [(gm, gn, g) for gm in range(1, 11) for gn in range(1, 8) for g in (1, 2, 3, 4, 5, 11)])
+def test_grouped_raster_is_the_sort_by_band_column_row(gm, gn, g):
+    want = sorted(((pm, pn) for pm in range(gm) for pn in range(gn)), key=lambda t: (t[0] // g, t[1], t[0]))
+    assert opm.raster_order(gm, gn, g, True) == want
+    assert opm.raster_order(gm, gn, g, False) == sorted((pm, pn) for pm in range(gm) for pn in range(gn))
+
+
+def test_special_cases():
+    for gm, gn in [(3, 7), (8, 8), (5, 5), (1, 9), (9, 1)]:
+        T = gm * gn
+        rowmajor = list(range(T))
+        colmajor = [pm * gn + pn for pn in range(gn) for pm in range(gm)]
+        assert opm.pid_map(gm, gn, 8, 4, opm.MODE_RR) == rowmajor
+        assert opm.pid_map(gm, gn, 1, 4, opm.MODE_XCD) == rowmajor            # one XCD: nothing to renumber
+        assert opm.pid_map(gm, gn, 8, 1, opm.MODE_GROUPM) == rowmajor         # bands of one row
+        assert opm.pid_map(gm, gn, 1, gm, opm.MODE_XCD_GROUPM) == colmajor    # one band: column-major
+        assert opm.pid_map(gm, gn, 8, gm + 3, opm.MODE_GROUPM) == colmajor
+        assert opm.pid_map(gm, gn, T + 5, 4, opm.MODE_XCD) == rowmajor        # fewer workgroups than XCDs
+        assert opm.pid_map(gm, gn, 8, 1, opm.MODE_XCD_GROUPM) == opm.pid_map(gm, gn, 8, 1, opm.MODE_XCD)
+
+
+@pytest.mark.parametrize("gm,gn", [(4, 4), (16, 16), (32, 32), (64, 8), (40, 28), (79, 55), (79, 28), (5, 5), (7, 3), (1, 1), (2, 3)])
+@pytest.mark.parametrize("X", [1, 3, 4, 8])
+@pytest.mark.parametrize("mode", [0, 1, 2, 3])
+def test_invariants(gm, gn, X, mode):
+    g = 4
+    out = opm.pid_map(gm, gn, X, g, mode)
+    T = gm * gn
+    assert opm.is_permutation(out, T)
+    assert opm.fair_share(out, X)
+    if mode in (1, 2):
+        assert opm.xcd_runs_contiguous(out, gm, gn, g, mode == 2, X)
+    if mode == 2:
+        # along the logical order, every aligned run inside a band stays in one tile column
+        inv = sorted(range(T), key=lambda w: opm.logical_ids(T, X, True)[w])
+        seq = [out[w] for w in inv]
+        assert seq == [pm * gn + pn for pm, pn in opm.raster_order(gm, gn, g, True)]
+
+
+def test_checkers_catch_planted_mistakes():
+    gm, gn, X, g = 6, 5, 4, 2
+    good = opm.pid_map(gm, gn, X, g, 2)
+    assert opm.xcd_runs_contiguous(good, gm, gn, g, True, X)
+    swapped = list(good)
+    swapped[0], swapped[1] = swapped[1], swapped[0]          # still a permutation, but XCD 0 and 1 trade a tile
+    assert opm.is_permutation(swapped, gm * gn)
+    assert not opm.xcd_runs_contiguous(swapped, gm, gn, g, True, X)
+    rr = opm.pid_map(gm, gn, X, g, 0)
+    assert not opm.xcd_runs_contiguous(rr, gm, gn, g, False, X)   # round-robin scatters neighbours
+    lopsided = [t for w, t in enumerate(good) if w % X != 1]      # XCD 1 loses its workgroups
+    assert opm.fair_share(good, X) and len(lopsided) % X != 0
+
+
+def test_bad_arguments_raise():
+    for args in [(0, 4, 8, 4, 0), (4, 0, 8, 4, 0), (4, 4, 0, 4, 1), (4, 4, 8, 0, 2), (4, 4, 8, 4, 4), (4, 4, 8, 4, -1)]:
+        with pytest.raises(ValueError):
+            opm.pid_map(*args)
