@@ -1,0 +1,111 @@
+/* libswz — XCD-aware swizzled bf16 GEMM for AMD Instinct MI355X (gfx950).
+ *
+ * C ABI.  No exception crosses it; every function that can fail returns a swz_status
+ * (0 = success, negative = error) and, on error, leaves its output buffers untouched.
+ *
+ * Background (SwizzlePerf, Introduction and Appendix "Case Study: GEMM Swizzling"): on a
+ * chiplet GPU the workgroups of a launch are handed to the XCDs round-robin, workgroup w to
+ * XCD (w mod X), and every XCD has a private L2.  Output tiles in one row of C read the same
+ * rows of A and tiles in one column read the same columns of B, so a kernel gains L2 reuse
+ * when it recomputes its program id such that the tiles an XCD works on are neighbours.
+ * "Hardware workgroup id" below is w (blockIdx.x of a 1-D launch); the "tile" is the
+ * (pm, pn) block of C that workgroup computes.
+ */
+#ifndef SWZ_H
+#define SWZ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Same declaration the HIP runtime headers make; repeating it keeps this header free of
+ * any HIP include.  Python callers pass the stream handle as a pointer-sized integer. */
+typedef struct ihipStream_t* hipStream_t;
+
+typedef enum {
+  SWZ_OK = 0,
+  SWZ_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, unknown mode                */
+  SWZ_ERR_UNSUPPORTED = -2, /* valid request this build cannot serve (dtype, alignment, tile) */
+  SWZ_ERR_OVERFLOW = -3,    /* a count does not fit the 32-bit index arithmetic              */
+  SWZ_ERR_HIP = -4          /* the HIP runtime reported an error (launch, attribute query)   */
+} swz_status;
+
+/* How hardware workgroup ids are turned into tiles. */
+typedef enum {
+  SWZ_MODE_RR = 0,         /* no renumbering, row-major raster: what round-robin dispatch gives by default */
+  SWZ_MODE_XCD = 1,        /* XCD renumbering (each XCD owns one contiguous run of the raster), row-major   */
+  SWZ_MODE_XCD_GROUPM = 2, /* XCD renumbering, grouped-M raster                                            */
+  SWZ_MODE_GROUPM = 3      /* no renumbering, grouped-M raster                                             */
+} swz_mode;
+
+typedef enum { SWZ_DTYPE_BF16 = 0 } swz_dtype; /* A, B, C bfloat16; accumulation in fp32 */
+
+/* Optional knobs for swz_gemm_ex / swz_gemm_plan.  A field equal to 0 means "library default". */
+typedef struct {
+  int32_t bm;      /* tile rows:    128 or 256 */
+  int32_t bn;      /* tile columns: 128 or 256 (bm == bn) */
+  int32_t bk;      /* K step: 64 */
+  int32_t group_m; /* tile rows per band of the grouped raster (default 4) */
+  int32_t num_xcd; /* XCD count assumed by the renumbering (default: detected; 8 on an unpartitioned MI355X) */
+} swz_params;
+
+const char* swz_status_string(int status);
+
+/* Facts about the current device that the remap depends on (the paper's "hardware context":
+ * XCD count, CUs, L2 size).  Any pointer may be null.  num_xcd is derived from the gfx950 CU
+ * count (32 CUs per XCD); l2_bytes is per XCD; lds_bytes is per workgroup. */
+int swz_device_info(int* num_xcd, int* compute_units, int* l2_bytes, int* lds_bytes);
+
+/* The PID map, computed on the host (GEMM swizzle of the paper's appendix, extended so that
+ * it is a bijection for every launch size, including sizes that are not a multiple of
+ * num_xcd, plus the grouped-M raster).
+ *   out : caller-owned HOST buffer of grid_m*grid_n int32; out[w] = pm*grid_n + pn.
+ *   mode 0/1 ignore group_m, mode 0/3 ignore num_xcd, but both must still be >= 1.
+ *   Renumbering: XCD x = w mod num_xcd receives n_x = q + [x < r] workgroups (q = T div X,
+ *   r = T mod X); its i-th workgroup (i = w div X) gets logical id  x*q + min(x,r) + i.
+ *   Grouped raster of logical id l: bands of group_m tile rows (last band shorter), inside a
+ *   band column by column, inside a column top to bottom.
+ * Errors: INVALID_ARG (null out, any argument < 1, unknown mode), OVERFLOW (grid_m*grid_n >= 2^31). */
+int swz_pid_map(int grid_m, int grid_n, int num_xcd, int group_m, int mode, int32_t* out);
+
+/* The same map evaluated by the DEVICE integer code the GEMM kernel uses: launches
+ * grid_m*grid_n workgroups; workgroup w writes d_tile[w] = pm*grid_n + pn and, if d_xcc is
+ * not null, d_xcc[w] = id of the XCD it actually ran on (hardware register XCC_ID).
+ *   d_tile, d_xcc : caller-owned DEVICE buffers of grid_m*grid_n int32.
+ * Asynchronous on `stream`; never allocates or synchronises.  Errors as swz_pid_map, plus HIP. */
+int swz_pid_map_device(int grid_m, int grid_n, int num_xcd, int group_m, int mode, int32_t* d_tile,
+                       int32_t* d_xcc, hipStream_t stream);
+
+/* C = A . B  (paper's GEMM case study: A is M x K, B is K x N, C is M x N), one workgroup per
+ * output tile, workgroup ids remapped according to `mode`.
+ *   A, B, C : caller-owned DEVICE pointers, row-major, densely packed (lda = K, ldb = N,
+ *             ldc = N), 16-byte aligned, bfloat16.  C is written completely (every element of
+ *             every tile, edge tiles masked); A and B are only read.  C must not alias A or B.
+ *   dtype   : SWZ_DTYPE_BF16.   mode : a swz_mode.
+ *   Products are accumulated in fp32 in ascending-k order per tile and rounded once to
+ *   bfloat16 (nearest even); the result bits do not depend on `mode`.
+ *   Defaults: num_xcd detected, group_m = 4, tile 256x256x64 (128x128x64 when M <= 512 and N <= 512).
+ * Asynchronous on `stream`; never allocates or synchronises.
+ * Errors: INVALID_ARG (null pointer, M/N/K < 1, unknown mode), UNSUPPORTED (other dtype,
+ * K or N not a multiple of 8, misaligned pointer), OVERFLOW (tile count >= 2^31 or a
+ * dimension >= 2^31), HIP. */
+int swz_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,
+             hipStream_t stream);
+
+/* swz_gemm with explicit tile shape / group_m / num_xcd (null params = all defaults).
+ * UNSUPPORTED for a tile shape other than 128x128x64 or 256x256x64. */
+int swz_gemm_ex(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,
+                const swz_params* params, hipStream_t stream);
+
+/* What swz_gemm_ex would launch for this problem: the resolved parameters and tile grid.
+ * Pure host arithmetic apart from the device query that resolves num_xcd = 0.
+ * Any output pointer may be null. */
+int swz_gemm_plan(int64_t M, int64_t N, int64_t K, const swz_params* params, swz_params* resolved,
+                  int* grid_m, int* grid_n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWZ_H */

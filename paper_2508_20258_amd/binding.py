@@ -1,0 +1,137 @@
+"""ctypes binding for libswz: same names as the C entry points, argument marshalling only.
+
+torch is used for device memory (``tensor.data_ptr()``) and streams only.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libswz.so")
+
+MODE_RR, MODE_XCD, MODE_XCD_GROUPM, MODE_GROUPM = 0, 1, 2, 3
+MODES = {"rr": MODE_RR, "xcd": MODE_XCD, "xcd_groupm": MODE_XCD_GROUPM, "groupm": MODE_GROUPM}
+DTYPE_BF16 = 0
+
+EXPORTS = ("swz_status_string", "swz_device_info", "swz_pid_map", "swz_pid_map_device", "swz_gemm", "swz_gemm_ex",
+           "swz_gemm_plan")
+
+
+class SwzParams(ctypes.Structure):
+    _fields_ = [("bm", ctypes.c_int32), ("bn", ctypes.c_int32), ("bk", ctypes.c_int32),
+                ("group_m", ctypes.c_int32), ("num_xcd", ctypes.c_int32)]
+
+
+class SwzError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2508_20258_amd.build` "
+            "(hipcc, gfx950). There is no fallback path.")
+    L = ctypes.CDLL(LIB_PATH)
+    i, i64, vp = ctypes.c_int, ctypes.c_int64, ctypes.c_void_p
+    ip = ctypes.POINTER(ctypes.c_int)
+    pp = ctypes.POINTER(SwzParams)
+    L.swz_status_string.argtypes = [i]
+    L.swz_status_string.restype = ctypes.c_char_p
+    L.swz_device_info.argtypes = [ip, ip, ip, ip]
+    L.swz_pid_map.argtypes = [i, i, i, i, i, vp]
+    L.swz_pid_map_device.argtypes = [i, i, i, i, i, vp, vp, vp]
+    L.swz_gemm.argtypes = [vp, vp, vp, i64, i64, i64, i, i, vp]
+    L.swz_gemm_ex.argtypes = [vp, vp, vp, i64, i64, i64, i, i, pp, vp]
+    L.swz_gemm_plan.argtypes = [i64, i64, i64, pp, pp, ip, ip]
+    for name in EXPORTS:
+        if name != "swz_status_string":
+            getattr(L, name).restype = i
+    return L
+
+
+lib = _load()
+
+
+def status_string(status: int) -> str:
+    return lib.swz_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise SwzError(status, where)
+
+
+def _stream_handle(stream) -> int:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _params(bm=0, bn=0, bk=0, group_m=0, num_xcd=0) -> SwzParams:
+    return SwzParams(int(bm), int(bn), int(bk), int(group_m), int(num_xcd))
+
+
+def device_info() -> dict:
+    v = [ctypes.c_int(0) for _ in range(4)]
+    _check(lib.swz_device_info(*[ctypes.byref(x) for x in v]), "swz_device_info")
+    return dict(num_xcd=v[0].value, compute_units=v[1].value, l2_bytes=v[2].value, lds_bytes=v[3].value)
+
+
+def pid_map(grid_m: int, grid_n: int, num_xcd: int, group_m: int, mode: int) -> np.ndarray:
+    """Host PID map: out[w] = pm*grid_n + pn (int32 numpy array)."""
+    n = int(grid_m) * int(grid_n)
+    out = np.full(max(n, 1) if 0 < n < (1 << 31) else 1, -1, dtype=np.int32)
+    _check(lib.swz_pid_map(int(grid_m), int(grid_n), int(num_xcd), int(group_m), int(mode), out.ctypes.data),
+           "swz_pid_map")
+    return out
+
+
+def pid_map_device(grid_m: int, grid_n: int, num_xcd: int, group_m: int, mode: int, stream=None):
+    """Device PID map: (tile, xcc) int32 CUDA tensors filled by the kernel's own decode."""
+    import torch
+    n = int(grid_m) * int(grid_n)
+    if not 0 < n < (1 << 31):
+        n = 1  # let the library report the error; keep the buffers valid
+    tile = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+    xcc = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+    _check(lib.swz_pid_map_device(int(grid_m), int(grid_n), int(num_xcd), int(group_m), int(mode), tile.data_ptr(),
+                                  xcc.data_ptr(), _stream_handle(stream)), "swz_pid_map_device")
+    return tile, xcc
+
+
+def gemm_plan(M: int, N: int, K: int, **params) -> dict:
+    r = SwzParams()
+    gm, gn = ctypes.c_int(0), ctypes.c_int(0)
+    p = _params(**params)
+    _check(lib.swz_gemm_plan(int(M), int(N), int(K), ctypes.byref(p), ctypes.byref(r), ctypes.byref(gm),
+                             ctypes.byref(gn)), "swz_gemm_plan")
+    return dict(bm=r.bm, bn=r.bn, bk=r.bk, group_m=r.group_m, num_xcd=r.num_xcd, grid_m=gm.value, grid_n=gn.value)
+
+
+def gemm(a, b, c=None, mode: int = MODE_XCD_GROUPM, stream=None, **params):
+    """C = A @ B on the GPU through swz_gemm / swz_gemm_ex.
+
+    a (M x K), b (K x N): contiguous torch.bfloat16 CUDA tensors; c (M x N) is allocated if not given.
+    Keyword params (bm, bn, bk, group_m, num_xcd) select swz_gemm_ex.
+    """
+    import torch
+    assert a.is_cuda and b.is_cuda and a.dtype == torch.bfloat16 and b.dtype == torch.bfloat16
+    assert a.is_contiguous() and b.is_contiguous() and a.dim() == 2 and b.dim() == 2 and a.shape[1] == b.shape[0]
+    M, K = a.shape
+    N = b.shape[1]
+    if c is None:
+        c = torch.empty((M, N), dtype=torch.bfloat16, device=a.device)
+    assert c.is_cuda and c.dtype == torch.bfloat16 and c.is_contiguous() and tuple(c.shape) == (M, N)
+    h = _stream_handle(stream)
+    if params:
+        p = _params(**params)
+        st = lib.swz_gemm_ex(a.data_ptr(), b.data_ptr(), c.data_ptr(), M, N, K, DTYPE_BF16, int(mode), ctypes.byref(p), h)
+        _check(st, "swz_gemm_ex")
+    else:
+        _check(lib.swz_gemm(a.data_ptr(), b.data_ptr(), c.data_ptr(), M, N, K, DTYPE_BF16, int(mode), h), "swz_gemm")
+    return c

@@ -1,0 +1,57 @@
+// Integer PID remap shared by the host entry point and every kernel of the library.
+//
+// Round-robin dispatch puts hardware workgroup w on XCD x = w mod X (SwizzlePerf,
+// Introduction; Appendix "Case Study: GEMM Swizzling").  The paper's closed form,
+// (w mod X) * ceil(T/X) + w div X, renumbers workgroups so that every XCD owns a contiguous
+// run of logical ids, but it leaves [0,T) whenever T is not a multiple of X.  The form below
+// is the same map when X divides T and stays a bijection for every T >= 1, X >= 1:
+//
+//   q = T div X, r = T mod X.  XCD x receives n_x = q + [x < r] workgroups, the i-th of them
+//   being w = i*X + x, so i ranges over [0, n_x).  Give XCD x the id interval starting at
+//   s_x = x*q + min(x, r).  Then s_0 = 0, s_{x+1} = s_x + n_x and s_X = T, so the intervals
+//   [s_x, s_x + n_x) tile [0, T) without gap or overlap and  w -> s_x + i  is a bijection.
+//   (T < X gives q = 0, r = T: the identity.)
+//
+// The grouped-M raster decodes a logical id l into a tile: rows are cut into bands of
+// group_m tile rows (the last band may be shorter, gsz rows); within a band l walks column
+// by column, top to bottom inside a column.  (k mod gsz, k div gsz) is the mixed-radix
+// decomposition of k in [0, gsz*grid_n), so each band, and hence the grid, is covered once.
+#pragma once
+
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define SWZ_HD __host__ __device__ __forceinline__
+#else
+#define SWZ_HD inline
+#endif
+
+enum : int { kModeRR = 0, kModeXcd = 1, kModeXcdGroupM = 2, kModeGroupM = 3 };
+
+// Requires: 1 <= grid_m, grid_n, num_xcd; 1 <= group_m <= grid_m; grid_m*grid_n < 2^31;
+// 0 <= w < grid_m*grid_n.  All intermediate values are <= grid_m*grid_n.
+SWZ_HD void swz_decode_tile(int w, int grid_m, int grid_n, int num_xcd, int group_m, int mode, int* pm, int* pn) {
+  const int total = grid_m * grid_n;
+  int l = w;
+  if (mode == kModeXcd || mode == kModeXcdGroupM) {
+    const int q = total / num_xcd;
+    const int r = total - q * num_xcd;
+    const int i = w / num_xcd;
+    const int x = w - i * num_xcd;
+    l = x * q + (x < r ? x : r) + i;
+  }
+  if (mode == kModeXcdGroupM || mode == kModeGroupM) {
+    const int width = group_m * grid_n;
+    const int band = l / width;
+    const int k = l - band * width;
+    const int first = band * group_m;
+    const int gsz = (grid_m - first < group_m) ? grid_m - first : group_m;
+    const int c = k / gsz;
+    *pm = first + (k - c * gsz);
+    *pn = c;
+  } else {
+    const int row = l / grid_n;
+    *pm = row;
+    *pn = l - row * grid_n;
+  }
+}

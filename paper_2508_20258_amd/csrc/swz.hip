@@ -1,0 +1,184 @@
+// libswz: C-ABI entry points (declared in include/swz.h).  Host side: argument checks,
+// tile choice, launches.  Nothing here allocates device memory or synchronises.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <mutex>
+
+#include "../../include/swz.h"
+#include "gemm_kernel.h"
+#include "pid_decode.h"
+
+namespace {
+
+constexpr int kCusPerXcd = 32;   // gfx950: 8 XCDs x 32 CUs
+constexpr int kMaxDevices = 64;
+
+struct DeviceFacts {
+  bool known = false;
+  int num_xcd = 0, cus = 0, l2_bytes = 0, lds_bytes = 0;
+};
+DeviceFacts g_facts[kMaxDevices];
+bool g_attr_set[kMaxDevices][2];
+std::mutex g_mu;
+
+int query_device(DeviceFacts* out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SWZ_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_mu);
+  DeviceFacts& f = g_facts[dev];
+  if (!f.known) {
+    int cus = 0, l2 = 0, lds = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return SWZ_ERR_HIP;
+    if (hipDeviceGetAttribute(&l2, hipDeviceAttributeL2CacheSize, dev) != hipSuccess) return SWZ_ERR_HIP;
+    if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return SWZ_ERR_HIP;
+    f.cus = cus;
+    f.l2_bytes = l2;
+    f.lds_bytes = lds;
+    // A partitioned device exposes fewer CUs; XCDs always come in whole units of 32 CUs.
+    f.num_xcd = cus >= kCusPerXcd ? cus / kCusPerXcd : 1;
+    f.known = true;
+  }
+  *out = f;
+  return SWZ_OK;
+}
+
+bool valid_mode(int mode) { return mode >= SWZ_MODE_RR && mode <= SWZ_MODE_GROUPM; }
+
+// Shared checks of the two PID-map entry points.  Clamps group_m to grid_m (same raster).
+int check_map_args(int grid_m, int grid_n, int num_xcd, int* group_m, int mode) {
+  if (grid_m < 1 || grid_n < 1 || num_xcd < 1 || *group_m < 1 || !valid_mode(mode)) return SWZ_ERR_INVALID_ARG;
+  if ((int64_t)grid_m * (int64_t)grid_n >= (int64_t)1 << 31) return SWZ_ERR_OVERFLOW;
+  if (*group_m > grid_m) *group_m = grid_m;
+  return SWZ_OK;
+}
+
+template <class S>
+int launch_gemm(const void* A, const void* B, void* C, int M, int N, int K, int grid_m, int grid_n,
+                int num_xcd, int group_m, int mode, hipStream_t stream, int slot) {
+  auto kernel = swz::gemm_bf16_kernel<S>;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SWZ_ERR_HIP;
+  {
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (!g_attr_set[dev][slot]) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              S::LDS_BYTES) != hipSuccess)
+        return SWZ_ERR_HIP;
+      g_attr_set[dev][slot] = true;
+    }
+  }
+  hipLaunchKernelGGL(kernel, dim3((unsigned)(grid_m * grid_n)), dim3(S::NT), S::LDS_BYTES, stream,
+                     static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(B), static_cast<uint16_t*>(C),
+                     M, N, K, grid_m, grid_n, num_xcd, group_m, mode);
+  return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
+}
+
+int resolve_plan(int64_t M, int64_t N, int64_t K, const swz_params* p, swz_params* r, int* grid_m, int* grid_n) {
+  if (M < 1 || N < 1 || K < 1) return SWZ_ERR_INVALID_ARG;
+  const int64_t lim = (int64_t)1 << 31;
+  if (M >= lim || N >= lim || K >= lim) return SWZ_ERR_OVERFLOW;
+  swz_params q = {0, 0, 0, 0, 0};
+  if (p != nullptr) q = *p;
+  if (q.bm < 0 || q.bn < 0 || q.bk < 0 || q.group_m < 0 || q.num_xcd < 0) return SWZ_ERR_INVALID_ARG;
+  if (q.bm == 0 && q.bn == 0) q.bm = q.bn = (M <= 512 && N <= 512) ? 128 : 256;
+  if (q.bm == 0) q.bm = q.bn;
+  if (q.bn == 0) q.bn = q.bm;
+  if (q.bk == 0) q.bk = swz::kBK;
+  if (q.group_m == 0) q.group_m = 4;
+  if (!((q.bm == 128 && q.bn == 128) || (q.bm == 256 && q.bn == 256)) || q.bk != swz::kBK) return SWZ_ERR_UNSUPPORTED;
+  if (q.num_xcd == 0) {
+    DeviceFacts f;
+    const int st = query_device(&f);
+    if (st != SWZ_OK) return st;
+    q.num_xcd = f.num_xcd;
+  }
+  const int64_t gm = (M + q.bm - 1) / q.bm, gn = (N + q.bn - 1) / q.bn;
+  if (gm * gn >= lim) return SWZ_ERR_OVERFLOW;
+  if (r != nullptr) *r = q;
+  if (grid_m != nullptr) *grid_m = (int)gm;
+  if (grid_n != nullptr) *grid_n = (int)gn;
+  return SWZ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* swz_status_string(int status) {
+  switch (status) {
+    case SWZ_OK: return "ok";
+    case SWZ_ERR_INVALID_ARG: return "invalid argument";
+    case SWZ_ERR_UNSUPPORTED: return "unsupported dtype, alignment or tile shape";
+    case SWZ_ERR_OVERFLOW: return "size does not fit 32-bit tile arithmetic";
+    case SWZ_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int swz_device_info(int* num_xcd, int* compute_units, int* l2_bytes, int* lds_bytes) {
+  DeviceFacts f;
+  const int st = query_device(&f);
+  if (st != SWZ_OK) return st;
+  if (num_xcd) *num_xcd = f.num_xcd;
+  if (compute_units) *compute_units = f.cus;
+  if (l2_bytes) *l2_bytes = f.l2_bytes;
+  if (lds_bytes) *lds_bytes = f.lds_bytes;
+  return SWZ_OK;
+}
+
+int swz_pid_map(int grid_m, int grid_n, int num_xcd, int group_m, int mode, int32_t* out) {
+  if (out == nullptr) return SWZ_ERR_INVALID_ARG;
+  const int st = check_map_args(grid_m, grid_n, num_xcd, &group_m, mode);
+  if (st != SWZ_OK) return st;
+  const int total = grid_m * grid_n;
+  for (int w = 0; w < total; ++w) {
+    int pm, pn;
+    swz_decode_tile(w, grid_m, grid_n, num_xcd, group_m, mode, &pm, &pn);
+    out[w] = pm * grid_n + pn;
+  }
+  return SWZ_OK;
+}
+
+int swz_pid_map_device(int grid_m, int grid_n, int num_xcd, int group_m, int mode, int32_t* d_tile,
+                       int32_t* d_xcc, hipStream_t stream) {
+  if (d_tile == nullptr) return SWZ_ERR_INVALID_ARG;
+  const int st = check_map_args(grid_m, grid_n, num_xcd, &group_m, mode);
+  if (st != SWZ_OK) return st;
+  hipLaunchKernelGGL(swz::pid_map_kernel, dim3((unsigned)(grid_m * grid_n)), dim3(64), 0, stream, grid_m, grid_n,
+                     num_xcd, group_m, mode, d_tile, d_xcc);
+  return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
+}
+
+int swz_gemm_plan(int64_t M, int64_t N, int64_t K, const swz_params* params, swz_params* resolved, int* grid_m,
+                  int* grid_n) {
+  return resolve_plan(M, N, K, params, resolved, grid_m, grid_n);
+}
+
+int swz_gemm_ex(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,
+                const swz_params* params, hipStream_t stream) {
+  if (A == nullptr || B == nullptr || C == nullptr || !valid_mode(mode)) return SWZ_ERR_INVALID_ARG;
+  swz_params r;
+  int grid_m = 0, grid_n = 0;
+  int st = resolve_plan(M, N, K, params, &r, &grid_m, &grid_n);
+  if (st != SWZ_OK) return st;
+  if (dtype != SWZ_DTYPE_BF16) return SWZ_ERR_UNSUPPORTED;
+  if ((K % 8) != 0 || (N % 8) != 0) return SWZ_ERR_UNSUPPORTED;   // 16-byte vector loads along k and n
+  if ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(C)) & 15)
+    return SWZ_ERR_UNSUPPORTED;
+  int group_m = r.group_m;
+  st = check_map_args(grid_m, grid_n, r.num_xcd, &group_m, mode);
+  if (st != SWZ_OK) return st;
+  if (r.bm == 128)
+    return launch_gemm<swz::GemmShape<128, 128, 2, 2>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
+                                                       group_m, mode, stream, 0);
+  return launch_gemm<swz::GemmShape<256, 256, 2, 4>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
+                                                     group_m, mode, stream, 1);
+}
+
+int swz_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,
+             hipStream_t stream) {
+  return swz_gemm_ex(A, B, C, M, N, K, dtype, mode, nullptr, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,225 @@
+"""GPU parity: libswz (through its C ABI) against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+import seeded_inputs as si
+from oracle import gemm_ref
+from oracle import pid_map as opm
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def swz():
+    import paper_2508_20258_amd as m
+    assert torch.cuda.is_available()
+    return m
+
+
+def to_dev(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def to_bits(t):
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def run_modes(swz, a_bits, b_bits, modes=(0, 1, 2, 3), **params):
+    a, b = to_dev(a_bits), to_dev(b_bits)
+    outs = {}
+    for mode in modes:
+        c = torch.full((a.shape[0], b.shape[1]), float("nan"), dtype=torch.bfloat16, device="cuda")
+        swz.gemm(a, b, c, mode=mode, **params)
+        torch.cuda.synchronize()
+        outs[mode] = to_bits(c)
+    return outs
+
+
+def assert_within_tolerance(c_bits, ref, what):
+    got = si.bf16_bits_to_f64(c_bits)
+    ok = gemm_ref.within_tolerance(got, ref)      # |got - ref| <= 1e-2 |ref| + 1e-2
+    assert ok.all(), f"{what}: {np.count_nonzero(~ok)} of {ok.size} outside tolerance, worst {np.abs(got - ref).max()}"
+
+
+# ---------------------------------------------------------------------------- PID map on device
+
+@pytest.mark.parametrize("gm,gn,X,g", [(4, 4, 8, 4), (16, 16, 8, 4), (32, 32, 8, 4), (64, 8, 8, 4), (40, 28, 8, 4),
+                                       (79, 55, 8, 4), (79, 28, 8, 4), (5, 5, 8, 4), (7, 3, 8, 4), (4, 5, 4, 4),
+                                       (1, 1, 8, 4), (3, 2, 8, 9), (33, 31, 5, 3)])
+def test_device_decode_is_bit_exact_with_oracle(swz, gm, gn, X, g):
+    for mode in range(4):
+        tile, _ = swz.pid_map_device(gm, gn, X, g, mode)
+        torch.cuda.synchronize()
+        assert tile.cpu().numpy().tolist() == opm.pid_map(gm, gn, X, g, mode), (gm, gn, X, g, mode)
+
+
+def test_hardware_dispatch_is_round_robin_over_xcds(swz):
+    info = swz.device_info()
+    X = info["num_xcd"]
+    assert X >= 1 and info["compute_units"] % X == 0
+    for gm, gn in [(16, 16), (40, 28), (79, 55)]:
+        _, xcc = swz.pid_map_device(gm, gn, X, 4, 0)
+        torch.cuda.synchronize()
+        xcc = xcc.cpu().numpy()
+        first = xcc[:X]
+        assert sorted(first.tolist()) == list(range(X))                  # a relabelling of 0..X-1
+        assert (xcc == first[np.arange(xcc.size) % X]).all()              # workgroup w runs on XCD (w mod X)
+
+
+def test_device_entry_point_error_paths(swz):
+    t = torch.full((16,), -7, dtype=torch.int32, device="cuda")
+    L = swz.lib
+    assert L.swz_pid_map_device(0, 4, 8, 4, 0, t.data_ptr(), None, None) == -1
+    assert L.swz_pid_map_device(4, 4, 8, 4, 5, t.data_ptr(), None, None) == -1
+    assert L.swz_pid_map_device(4, 4, 8, 4, 0, None, None, None) == -1
+    assert L.swz_pid_map_device(1 << 16, 1 << 15, 8, 4, 0, t.data_ptr(), None, None) == -3
+    torch.cuda.synchronize()
+    assert (t.cpu().numpy() == -7).all()
+    assert L.swz_pid_map_device(4, 4, 8, 4, 1, t.data_ptr(), None, None) == 0    # xcc buffer is optional
+    torch.cuda.synchronize()
+    assert t.cpu().numpy().tolist() == opm.pid_map(4, 4, 8, 4, 1)
+
+
+# ---------------------------------------------------------------------------- GEMM, full-matrix checks
+
+def test_config1_512_all_modes_full_matrix(swz):
+    a, b = si.config_inputs("cfg1_512")
+    ref = gemm_ref.gemm(a, b)
+    outs = run_modes(swz, a, b)
+    for mode, c in outs.items():
+        assert_within_tolerance(c, ref, f"cfg1 mode {mode}")
+        assert np.array_equal(c, outs[0]), f"mode {mode} differs bitwise from round-robin"
+    plan = swz.gemm_plan(512, 512, 512)
+    assert (plan["bm"], plan["bn"], plan["bk"], plan["grid_m"], plan["grid_n"]) == (128, 128, 64, 4, 4)
+
+
+@pytest.mark.parametrize("tile", [128, 256])
+@pytest.mark.parametrize("M,N,K", [(300, 520, 192), (1, 8, 8), (257, 264, 72), (640, 776, 200), (513, 1032, 64)])
+def test_ragged_shapes_full_matrix(swz, tile, M, N, K):
+    # several tiles and a ragged tail in every dimension (K tail included: K % 64 != 0)
+    a = si.matrix_bf16(100 + M, 0, M, K, "uniform")
+    b = si.matrix_bf16(100 + M, 1, K, N, "normal", 0.5)
+    ref = gemm_ref.gemm(a, b)
+    outs = run_modes(swz, a, b, bm=tile, bn=tile)
+    for mode, c in outs.items():
+        assert_within_tolerance(c, ref, f"{M}x{N}x{K} tile {tile} mode {mode}")
+        assert np.array_equal(c, outs[0])
+
+
+@pytest.mark.parametrize("tile", [128, 256])
+def test_small_integer_inputs_are_bit_exact(swz, tile):
+    # entries in {-1,0,1}, K <= 256: every partial sum is an integer below 2^8, exact in fp32 and in bf16
+    M, N, K = 520, 392, 256
+    a = si.small_int_matrix_bf16(7, 0, M, K)
+    b = si.small_int_matrix_bf16(7, 1, K, N)
+    ref = gemm_ref.gemm(a, b)
+    for mode, c in run_modes(swz, a, b, bm=tile, bn=tile).items():
+        assert np.array_equal(si.bf16_bits_to_f64(c), ref), f"mode {mode}"
+
+
+@pytest.mark.parametrize("tile", [128, 256])
+def test_one_hot_b_copies_columns_of_a(swz, tile):
+    # B = column selector: C[:, j] = A[:, perm[j]] exactly; catches any fragment-layout or transpose slip
+    M, K = 384, 320
+    N = K
+    a = si.matrix_bf16(9, 0, M, K, "normal")
+    perm = np.random.default_rng(3).permutation(K)
+    sel = np.zeros((K, N), dtype=np.float32)
+    sel[perm, np.arange(N)] = 1.0
+    b = si.f32_to_bf16_bits(sel)
+    ref = gemm_ref.gemm(a, b)
+    assert np.array_equal(ref, si.bf16_bits_to_f64(a)[:, perm])
+    for mode, c in run_modes(swz, a, b, modes=(0, 2), bm=tile, bn=tile).items():
+        assert np.array_equal(c, a[:, perm]), f"mode {mode}"
+
+
+def test_all_ones_gives_k(swz):
+    M, N, K = 256, 512, 256
+    one = si.f32_to_bf16_bits(np.ones((max(M, K), max(K, N)), dtype=np.float32))
+    outs = run_modes(swz, one[:M, :K], one[:K, :N], modes=(2,))
+    assert (si.bf16_bits_to_f64(outs[2]) == float(K)).all()
+
+
+def test_other_xcd_counts_and_group_sizes_do_not_change_the_bits(swz):
+    M, N, K = 1100, 904, 128
+    a = si.matrix_bf16(21, 0, M, K, "normal")
+    b = si.matrix_bf16(21, 1, K, N, "normal")
+    ref = gemm_ref.gemm(a, b)
+    base = run_modes(swz, a, b, modes=(0,), bm=128, bn=128)[0]
+    assert_within_tolerance(base, ref, "base")
+    for X, g in [(1, 1), (3, 2), (8, 7), (5, 100), (64, 4)]:
+        outs = run_modes(swz, a, b, modes=(1, 2, 3), bm=128, bn=128, num_xcd=X, group_m=g)
+        for mode, c in outs.items():
+            assert np.array_equal(c, base), (X, g, mode)
+
+
+def test_repeated_launches_are_deterministic(swz):
+    a, b = si.config_inputs("cfg1_512")
+    first = run_modes(swz, a, b, modes=(2,), bm=256, bn=256)[2]
+    for _ in range(3):
+        assert np.array_equal(run_modes(swz, a, b, modes=(2,), bm=256, bn=256)[2], first)
+
+
+def test_gemm_error_paths_leave_c_untouched(swz):
+    a = to_dev(si.matrix_bf16(1, 0, 64, 64, "uniform"))
+    c = torch.full((64, 64), 3.0, dtype=torch.bfloat16, device="cuda")
+    L = swz.lib
+    s = torch.cuda.current_stream().cuda_stream
+    assert L.swz_gemm(a.data_ptr(), a.data_ptr(), c.data_ptr(), 64, 64, 64, 0, 9, s) == -1
+    assert L.swz_gemm(a.data_ptr(), a.data_ptr(), c.data_ptr(), 64, 64, 60, 0, 0, s) == -2
+    assert L.swz_gemm(a.data_ptr(), a.data_ptr(), c.data_ptr(), 64, 64, 64, 3, 0, s) == -2
+    torch.cuda.synchronize()
+    assert (c == 3.0).all()
+
+
+# ---------------------------------------------------------------------------- GEMM, full-size workloads
+
+def sample_indices(M, N, bm, bn, seed, n=4096):
+    """Seeded random elements plus the corners of the matrix and of the first/last tiles."""
+    rng = np.random.default_rng(seed)
+    ii = rng.integers(0, M, n)
+    jj = rng.integers(0, N, n)
+    edge_r = [0, 1, bm - 1, bm, M - bm - 1 if M > bm else 0, M - 2, M - 1]
+    edge_c = [0, 1, bn - 1, bn, N - bn - 1 if N > bn else 0, N - 2, N - 1]
+    ei, ej = np.meshgrid(np.clip(edge_r, 0, M - 1), np.clip(edge_c, 0, N - 1), indexing="ij")
+    return np.concatenate([ii, ei.ravel()]), np.concatenate([jj, ej.ravel()])
+
+
+@pytest.mark.parametrize("name", ["cfg2_4096", "cfg3_8192", "cfg4_skinny", "cfg5_ragged"])
+def test_full_size_workloads_sampled_against_oracle_and_bit_identical_across_modes(swz, name):
+    cfg = si.CONFIGS[name]
+    M, N, K = cfg["M"], cfg["N"], cfg["K"]
+    a, b = si.config_inputs(name)
+    outs = run_modes(swz, a, b)                       # the launch configuration the benchmark times
+    plan = swz.gemm_plan(M, N, K)
+    assert (plan["bm"], plan["bn"], plan["bk"]) == cfg["tile"]
+    for mode in (1, 2, 3):
+        assert np.array_equal(outs[mode], outs[0]), f"{name}: mode {mode} differs bitwise from round-robin"
+    c = outs[0]
+    ii, jj = sample_indices(M, N, plan["bm"], plan["bn"], seed=cfg["seed"])
+    ref = gemm_ref.gemm_elems(a, b, ii, jj)
+    assert_within_tolerance(c[ii, jj], ref, f"{name} samples")
+    # whole first and last tile-row strip and tile-column strip (the masked edge tiles when ragged)
+    rows = 16 if M % plan["bm"] == 0 else M % plan["bm"]
+    cols = 16 if N % plan["bn"] == 0 else N % plan["bn"]
+    assert_within_tolerance(c[M - rows:], gemm_ref.gemm(a[M - rows:], b), f"{name} bottom strip")
+    assert_within_tolerance(c[:, N - cols:], gemm_ref.gemm(a, np.ascontiguousarray(b[:, N - cols:])), f"{name} right strip")
+    assert not np.isnan(si.bf16_bits_to_f64(c)).any()   # every element of C was written
+
+
+def test_config5_with_128_tiles_has_a_ragged_xcd_share(swz):
+    # 79 x 55 = 4345 tiles = 8*543 + 1: XCD 0 gets one workgroup more than the others
+    cfg = si.CONFIGS["cfg5_ragged"]
+    M, N, K = cfg["M"], cfg["N"], 512            # shorter K: the point here is the grid, not the sum
+    a = si.matrix_bf16(4, 0, M, K, "uniform")
+    b = si.matrix_bf16(4, 1, K, N, "uniform")
+    plan = swz.gemm_plan(M, N, K, bm=128, bn=128)
+    assert (plan["grid_m"] * plan["grid_n"]) % plan["num_xcd"] != 0
+    outs = run_modes(swz, a, b, bm=128, bn=128)
+    for mode in (1, 2, 3):
+        assert np.array_equal(outs[mode], outs[0])
+    ii, jj = sample_indices(M, N, 128, 128, seed=5)
+    assert_within_tolerance(outs[0][ii, jj], gemm_ref.gemm_elems(a, b, ii, jj), "cfg5/128 samples")
+    assert not np.isnan(si.bf16_bits_to_f64(outs[0])).any()
