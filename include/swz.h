@@ -105,6 +105,13 @@ int swz_gemm_ex(const void* A, const void* B, void* C, int64_t M, int64_t N, int
 int swz_gemm_plan(int64_t M, int64_t N, int64_t K, const swz_params* params, swz_params* resolved,
                   int* grid_m, int* grid_n);
 
+/* Measurement aid, not part of the GEMM path: a plain streaming copy of `bytes` bytes
+ * (reads `bytes`, writes `bytes`; both DEVICE pointers 16-byte aligned, bytes a multiple of
+ * 16, buffers must not overlap).  The profiling harness scales the profiler's HBM byte
+ * counters by what they read for this kernel of known traffic.
+ * Asynchronous on `stream`.  Errors: INVALID_ARG (null, bytes < 16), UNSUPPORTED (alignment), HIP. */
+int swz_copy_bytes(const void* src, void* dst, int64_t bytes, hipStream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,7 +17,7 @@ MODES = {"rr": MODE_RR, "xcd": MODE_XCD, "xcd_groupm": MODE_XCD_GROUPM, "groupm"
 DTYPE_BF16 = 0
 
 EXPORTS = ("swz_status_string", "swz_device_info", "swz_pid_map", "swz_pid_map_device", "swz_gemm", "swz_gemm_ex",
-           "swz_gemm_plan")
+           "swz_gemm_plan", "swz_copy_bytes")
 
 
 class SwzParams(ctypes.Structure):
@@ -31,7 +31,24 @@ class SwzError(RuntimeError):
         super().__init__(f"{where}: {status_string(status)} ({status})")
 
 
+def _ensure_hip_runtime() -> None:
+    """libswz.so leaves its hip* symbols to the process: make one HIP runtime globally visible.
+
+    torch's streams and allocations belong to the runtime torch ships, so that is the one the
+    library must bind to; re-opening it with RTLD_GLOBAL exposes its symbols to libswz.so.
+    """
+    try:
+        import torch
+        path = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+        if not os.path.exists(path):
+            path = "libamdhip64.so"
+    except ImportError:  # no torch: a plain ROCm install
+        path = "libamdhip64.so"
+    ctypes.CDLL(path, mode=ctypes.RTLD_GLOBAL)
+
+
 def _load() -> ctypes.CDLL:
+    _ensure_hip_runtime()
     if not os.path.exists(LIB_PATH):
         raise ImportError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2508_20258_amd.build` "
@@ -48,6 +65,7 @@ def _load() -> ctypes.CDLL:
     L.swz_gemm.argtypes = [vp, vp, vp, i64, i64, i64, i, i, vp]
     L.swz_gemm_ex.argtypes = [vp, vp, vp, i64, i64, i64, i, i, pp, vp]
     L.swz_gemm_plan.argtypes = [i64, i64, i64, pp, pp, ip, ip]
+    L.swz_copy_bytes.argtypes = [vp, vp, i64, vp]
     for name in EXPORTS:
         if name != "swz_status_string":
             getattr(L, name).restype = i
@@ -135,3 +153,10 @@ def gemm(a, b, c=None, mode: int = MODE_XCD_GROUPM, stream=None, **params):
     else:
         _check(lib.swz_gemm(a.data_ptr(), b.data_ptr(), c.data_ptr(), M, N, K, DTYPE_BF16, int(mode), h), "swz_gemm")
     return c
+
+
+def copy_bytes(src, dst, stream=None) -> None:
+    """Plain device copy of src into dst (same byte size), the calibration kernel of known traffic."""
+    nbytes = src.numel() * src.element_size()
+    assert src.is_cuda and dst.is_cuda and dst.numel() * dst.element_size() == nbytes
+    _check(lib.swz_copy_bytes(src.data_ptr(), dst.data_ptr(), nbytes, _stream_handle(stream)), "swz_copy_bytes")

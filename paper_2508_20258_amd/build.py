@@ -14,6 +14,10 @@ HEADERS = ["gemm_kernel.h", "pid_decode.h", os.path.join("..", "..", "include", 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+    # The library does not name a HIP runtime of its own: its hip* symbols bind to the runtime
+    # the host process already uses (torch ships one), so kernels, streams and events all live in
+    # one runtime.  A C program that links libswz links libamdhip64 itself.
+    "-no-hip-rt",
     # packed-fp32 instructions are kept out of every kernel of this library
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",

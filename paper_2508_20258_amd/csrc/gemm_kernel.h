@@ -5,20 +5,40 @@
 // hardware workgroup id into a tile (pid_decode.h); nothing after that depends on the
 // mapping mode, so every mode produces the same bits.
 //
-// Per K step of 64 the workgroup stages an A tile (BM x 64) and a B tile (64 x BN) in LDS,
-// two stages deep: the global loads of step t+1 are in flight while the MFMAs of step t run.
+// Staging.  Per K step of 64 the workgroup needs an A tile (BM x 64) and a B tile (64 x BN).
+// They are copied global -> LDS by the memory pipeline itself (global_load_lds_dwordx4: each
+// lane's 16 bytes land at  M0 base + lane*16, no VGPRs involved), two stages deep, so the
+// loads of step t+1 are in flight while the MFMAs of step t run.  A lane cannot choose where
+// its bytes land, only what it fetches, so the XOR swizzle of the LDS layout is applied on the
+// global-address side: the lane that owns slot p of a row fetches chunk p ^ key(row).
+// Out-of-range chunks (rows >= M, columns >= N, k >= K) are fetched from a 16-byte block of
+// zeros, which keeps every address valid and makes the K tail exact.
 //
-// MFMA operand layout (v_mfma_f32_32x32x16_bf16, lane l of 64):
-//   A operand: 8 bf16 = A[row = l%32][k = 8*(l/32) .. +7]   -> one 16-byte LDS read (A is k-contiguous)
-//   B operand: 8 bf16 = B[k = 8*(l/32) .. +7][col = l%32]   -> B is n-contiguous in memory, so
-//              the fragment is fetched with two transposing LDS reads (ds_read_b64_tr_b16):
-//              inside each 16-lane group, lane s supplies the address of 4 consecutive
-//              columns of row s/4, and lane i receives rows 0..3 of column i.
-//   D: lane l, register v holds C[row = 8*(v/4) + 4*(l/32) + v%4][col = l%32].
+// MFMA (v_mfma_f32_32x32x16_bf16, lane l of 64).  Each operand register holds, for one row
+// (or column) index l%32, the 8 consecutive k values 8*(l/32) .. +7:
+//   fragment of A: A[m = l%32][k..]   -> one 16-byte LDS read (A is k-contiguous)
+//   fragment of B: B[k..][n = l%32]   -> B is n-contiguous, so it is fetched with two
+//       transposing LDS reads (ds_read_b64_tr_b16): inside each 16-lane group, lane s
+//       supplies the address of 4 consecutive columns of row s/4, and lane i receives
+//       rows 0..3 of column i.
+// The B fragment is passed as the instruction's first operand and the A fragment as its
+// second, i.e. the instruction computes the 32x32 block of C transposed: lane l, register v
+// then holds C[m = l%32][n = 8*(v/4) + 4*(l/32) + v%4], four consecutive columns per
+// register quad, which packs into one 8-byte store.
 //
-// LDS layouts (16-byte chunks, XOR-swizzled so that the read patterns above spread over banks):
-//   A: row r at byte r*128, chunk c (8 k-values) stored at chunk slot c ^ ((r ^ (r>>3)) & 7)
-//   B: row k at byte k*BN*2, chunk c (8 columns) stored at chunk slot c ^ ((k & 3) << 2)
+// Main loop.  Fragments are double buffered in registers: while the MFMAs of k-block kk run,
+// the LDS reads of k-block kk+1 are issued.  The workgroup barrier of a K step sits before
+// its last k-block: by then every wave has issued all its reads of the current stage, so the
+// stage can be refilled right after the barrier, and the reads of the next stage's first
+// k-block overlap the last MFMAs.
+//
+// Epilogue.  Each wave converts its accumulators to bf16 (nearest even), writes them to a
+// wave-private LDS patch and reads them back row-wise, so that global stores are 16 bytes
+// per lane and cover whole 128-byte lines.
+//
+// LDS layouts (16-byte chunks, XOR-swizzled so that the read patterns spread over banks):
+//   A: row r at byte r*128, chunk c (8 k-values) stored in slot c ^ ((r ^ (r>>3)) & 7)
+//   B: row k at byte k*BN*2, chunk c (8 columns) stored in slot c ^ ((k & 3) << 2)
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -29,28 +49,40 @@
 namespace swz {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int kBK = 64;
+constexpr int kKK = kBK / 16;  // MFMA k-blocks per K step
+
+// Source of every out-of-range 16-byte chunk.
+__device__ const u32x4 kZeroChunk = {0u, 0u, 0u, 0u};
 
 template <int BM_, int BN_, int WM_, int WN_>
 struct GemmShape {
   static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
-  static constexpr int NT = WM * WN * 64;          // threads per workgroup
+  static constexpr int NW = WM * WN;               // waves per workgroup
+  static constexpr int NT = NW * 64;               // threads per workgroup
   static constexpr int TM = BM / WM / 32;          // 32x32 blocks per wave, rows
   static constexpr int TN = BN / WN / 32;          // 32x32 blocks per wave, columns
   static constexpr int A_BYTES = BM * kBK * 2;
   static constexpr int B_BYTES = kBK * BN * 2;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-  static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
   static constexpr int B_ROW_CHUNKS = BN / 8;      // 16-byte chunks per B row
   static constexpr int A_LOADS = BM * 8 / NT;      // 16-byte chunks each thread moves per step
   static constexpr int B_LOADS = kBK * B_ROW_CHUNKS / NT;
+  // epilogue patch of one wave: (TM*32) rows of (TN*32) bf16, row pitch padded by 16 bytes
+  static constexpr int EPI_PITCH = TN * 32 * 2 + 16;
+  static constexpr int EPI_WAVE_BYTES = TM * 32 * EPI_PITCH;
+  static constexpr int EPI_BYTES = NW * EPI_WAVE_BYTES;
+  static constexpr int LDS_BYTES = 2 * STAGE_BYTES > EPI_BYTES ? 2 * STAGE_BYTES : EPI_BYTES;
   static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "wave tiling");
   static_assert((BM * 8) % NT == 0 && (kBK * B_ROW_CHUNKS) % NT == 0, "load tiling");
+  static_assert(TN * 32 * 2 / 16 <= 64 && 64 % (TN * 32 * 2 / 16) == 0, "epilogue row must divide a wave");
 };
 
 __device__ __forceinline__ int a_lds_off(int row, int chunk) {
@@ -66,13 +98,22 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const unsigned char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
 }
 
+// 16 bytes per lane, global -> LDS at (wave-uniform) lds_base + lane*16.
+// Written as inline assembly on purpose: the compiler then keeps no book on these loads, so it
+// does not guard later LDS reads of the *other* stage with a conservative vmcnt(0); the kernel
+// waits for them itself (s_waitcnt vmcnt(0) before the barrier that publishes a stage).
+__device__ __forceinline__ void load_to_lds(const void* gptr, unsigned char* lds_base) {
+  const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_base;
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory", "m0");
+}
+
 template <class S>
 __global__ __launch_bounds__(S::NT) void gemm_bf16_kernel(const uint16_t* __restrict__ A,
                                                           const uint16_t* __restrict__ B,
                                                           uint16_t* __restrict__ C, int M, int N, int K,
                                                           int grid_m, int grid_n, int num_xcd, int group_m,
                                                           int mode) {
-  constexpr int BM = S::BM, BN = S::BN, TM = S::TM, TN = S::TN, NT = S::NT;
+  constexpr int BM = S::BM, BN = S::BN, TM = S::TM, TN = S::TN;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
   int pm, pn;
@@ -82,44 +123,51 @@ __global__ __launch_bounds__(S::NT) void gemm_bf16_kernel(const uint16_t* __rest
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / S::WN;
   const int wn = wave % S::WN;
 
-  // ---- global -> register staging (each thread owns fixed chunks of the A and B tiles) ----
-  u32x4 ra[S::A_LOADS], rb[S::B_LOADS];
-  auto load_tile = [&](int k0) {
+  // ---- global -> LDS staging: which chunk of the tile this lane fetches for each of its loads ----
+  // Load i of wave w fills LDS bytes [(w*LOADS + i)*1024, +1024) of the A (resp. B) region.
+  const unsigned char* a_src[S::A_LOADS];
+  const unsigned char* b_src[S::B_LOADS];
+  bool a_ok[S::A_LOADS], b_ok[S::B_LOADS];
+  int a_k[S::A_LOADS], b_k[S::B_LOADS];       // k offset of the chunk inside a K step
 #pragma unroll
-    for (int i = 0; i < S::A_LOADS; ++i) {
-      const int q = tid + NT * i;
-      const int row = q >> 3, c = q & 7;
-      const int gr = m0 + row, gk = k0 + c * 8;
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (gr < M && gk < K) v = *reinterpret_cast<const u32x4*>(A + (size_t)gr * K + gk);
-      ra[i] = v;
-    }
+  for (int i = 0; i < S::A_LOADS; ++i) {
+    const int q = (wave * S::A_LOADS + i) * 64 + lane;
+    const int row = q >> 3, slot = q & 7;
+    const int c = slot ^ ((row ^ (row >> 3)) & 7);
+    a_ok[i] = (m0 + row) < M;
+    a_k[i] = c * 8;
+    a_src[i] = reinterpret_cast<const unsigned char*>(A + (size_t)(a_ok[i] ? m0 + row : 0) * K + c * 8);
+  }
 #pragma unroll
-    for (int i = 0; i < S::B_LOADS; ++i) {
-      const int q = tid + NT * i;
-      const int row = q / S::B_ROW_CHUNKS, c = q % S::B_ROW_CHUNKS;
-      const int gk = k0 + row, gn = n0 + c * 8;
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (gk < K && gn < N) v = *reinterpret_cast<const u32x4*>(B + (size_t)gk * N + gn);
-      rb[i] = v;
-    }
-  };
-  auto store_tile = [&](int stage) {
+  for (int i = 0; i < S::B_LOADS; ++i) {
+    const int q = (wave * S::B_LOADS + i) * 64 + lane;
+    const int krow = q / S::B_ROW_CHUNKS, slot = q % S::B_ROW_CHUNKS;
+    const int c = slot ^ ((krow & 3) << 2);
+    b_ok[i] = (n0 + c * 8) < N;
+    b_k[i] = krow;
+    b_src[i] = reinterpret_cast<const unsigned char*>(B + (size_t)krow * N + (b_ok[i] ? n0 + c * 8 : 0));
+  }
+  const size_t a_step = (size_t)kBK * 2;          // bytes per K step along a row of A
+  const size_t b_step = (size_t)kBK * N * 2;      // bytes per K step down the rows of B
+  const unsigned char* zero = reinterpret_cast<const unsigned char*>(&kZeroChunk);
+
+  auto issue_loads = [&](int kt, int stage) {
     unsigned char* sA = smem + stage * S::STAGE_BYTES;
     unsigned char* sB = sA + S::A_BYTES;
+    const int k0 = kt * kBK;
 #pragma unroll
     for (int i = 0; i < S::A_LOADS; ++i) {
-      const int q = tid + NT * i;
-      *reinterpret_cast<u32x4*>(sA + a_lds_off(q >> 3, q & 7)) = ra[i];
+      const bool ok = a_ok[i] && (k0 + a_k[i] < K);
+      load_to_lds(ok ? a_src[i] + kt * a_step : zero, sA + (wave * S::A_LOADS + i) * 1024);
     }
 #pragma unroll
     for (int i = 0; i < S::B_LOADS; ++i) {
-      const int q = tid + NT * i;
-      *reinterpret_cast<u32x4*>(sB + b_lds_off<BN>(q / S::B_ROW_CHUNKS, q % S::B_ROW_CHUNKS)) = rb[i];
+      const bool ok = b_ok[i] && (k0 + b_k[i] < K);
+      load_to_lds(ok ? b_src[i] + kt * b_step : zero, sB + (wave * S::B_LOADS + i) * 1024);
     }
   };
 
@@ -137,60 +185,91 @@ __global__ __launch_bounds__(S::NT) void gemm_bf16_kernel(const uint16_t* __rest
   const int b_krow0 = 8 * (lane >> 5) + ((lane & 15) >> 2); // + 16*kk (+4 for the upper half)
   const int b_col0 = wn * (TN * 32) + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // + 32*bj
 
-  const int KT = (K + kBK - 1) / kBK;
-  load_tile(0);
-  store_tile(0);
-  __syncthreads();
-
-  for (int kt = 0; kt < KT; ++kt) {
-    const int stage = kt & 1;
-    if (kt + 1 < KT) load_tile((kt + 1) * kBK);
-
+  bf16x8 af[2][TM], bfr[2][TN];
+  auto read_frags = [&](int buf, int stage, int kk) {
     const unsigned char* sA = smem + stage * S::STAGE_BYTES;
     const unsigned char* sB = sA + S::A_BYTES;
 #pragma unroll
-    for (int kk = 0; kk < kBK / 16; ++kk) {
-      bf16x8 af[TM], bfr[TN];
+    for (int bi = 0; bi < TM; ++bi)
+      af[buf][bi] = *reinterpret_cast<const bf16x8*>(sA + a_lds_off(a_row0 + 32 * bi, a_kc0 + 2 * kk));
 #pragma unroll
-      for (int bi = 0; bi < TM; ++bi) {
-        const int row = a_row0 + 32 * bi;
-        af[bi] = *reinterpret_cast<const bf16x8*>(sA + a_lds_off(row, a_kc0 + 2 * kk));
-      }
-#pragma unroll
-      for (int bj = 0; bj < TN; ++bj) {
-        const int col = b_col0 + 32 * bj;
-        const int kr = b_krow0 + 16 * kk;
-        const s16x4 lo = lds_read_tr16(sB + b_lds_off<BN>(kr, col >> 3) + (col & 7) * 2);
-        const s16x4 hi = lds_read_tr16(sB + b_lds_off<BN>(kr + 4, col >> 3) + (col & 7) * 2);
-        const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        bfr[bj] = __builtin_bit_cast(bf16x8, both);
-      }
-#pragma unroll
-      for (int bi = 0; bi < TM; ++bi)
-#pragma unroll
-        for (int bj = 0; bj < TN; ++bj)
-          acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[bi], bfr[bj], acc[bi][bj], 0, 0, 0);
+    for (int bj = 0; bj < TN; ++bj) {
+      const int col = b_col0 + 32 * bj;
+      const int kr = b_krow0 + 16 * kk;
+      const s16x4 lo = lds_read_tr16(sB + b_lds_off<BN>(kr, col >> 3) + (col & 7) * 2);
+      const s16x4 hi = lds_read_tr16(sB + b_lds_off<BN>(kr + 4, col >> 3) + (col & 7) * 2);
+      bfr[buf][bj] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     }
+  };
+  auto mfmas = [&](int buf) {
+#pragma unroll
+    for (int bi = 0; bi < TM; ++bi)
+#pragma unroll
+      for (int bj = 0; bj < TN; ++bj)
+        acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[buf][bj], af[buf][bi], acc[bi][bj], 0, 0, 0);
+  };
+  // Ask the scheduler to alternate one MFMA with one LDS read over a k-block.
+  auto interleave = [&]() {
+#pragma unroll
+    for (int i = 0; i < TM * TN; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+    }
+  };
 
-    if (kt + 1 < KT) store_tile(stage ^ 1);
+  const int KT = (K + kBK - 1) / kBK;
+  issue_loads(0, 0);
+  __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): stage 0 has landed (this wave's part)
+  __syncthreads();                      // ... and everybody else's
+  if (KT > 1) issue_loads(1, 1);
+  read_frags(0, 0, 0);
+
+  for (int kt = 0; kt < KT; ++kt) {
+    const int stage = kt & 1;
+#pragma unroll
+    for (int kk = 0; kk < kKK - 1; ++kk) {
+      read_frags((kk + 1) & 1, stage, kk + 1);
+      mfmas(kk & 1);
+      interleave();
+    }
+    // Every wave has issued all its reads of `stage`; the other stage must have landed.
+    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
     __syncthreads();
+    if (kt + 2 < KT) issue_loads(kt + 2, stage);
+    if (kt + 1 < KT) read_frags(0, stage ^ 1, 0);
+    mfmas((kKK - 1) & 1);
+    interleave();
   }
 
-  // ---- epilogue: fp32 -> bf16 (nearest even), masked stores ----
+  // ---- epilogue: fp32 -> bf16 (nearest even), transpose through a wave-private LDS patch ----
+  __syncthreads();   // all waves are done with the stage buffers the patches overlay
+  unsigned char* patch = smem + wave * S::EPI_WAVE_BYTES;
 #pragma unroll
   for (int bi = 0; bi < TM; ++bi) {
 #pragma unroll
     for (int bj = 0; bj < TN; ++bj) {
-      const int col = n0 + wn * (TN * 32) + 32 * bj + (lane & 31);
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = m0 + wm * (TM * 32) + 32 * bi + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (row < M && col < N) {
-          const __bf16 h = (__bf16)acc[bi][bj][v];
-          C[(size_t)row * N + col] = __builtin_bit_cast(uint16_t, h);
-        }
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 h;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) h[e] = (__bf16)acc[bi][bj][4 * g + e];
+        const int r = 32 * bi + (lane & 31);
+        const int ccol = 32 * bj + 8 * g + 4 * (lane >> 5);
+        *reinterpret_cast<bf16x4*>(patch + r * S::EPI_PITCH + ccol * 2) = h;
       }
     }
+  }
+  __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this wave's patch is written (wave-private, no barrier)
+  constexpr int ROW_CHUNKS = TN * 32 * 2 / 16;      // 16-byte chunks per patch row
+  constexpr int ROWS_PER_PASS = 64 / ROW_CHUNKS;
+  const int er = lane / ROW_CHUNKS, ec = lane % ROW_CHUNKS;
+#pragma unroll
+  for (int p = 0; p < TM * 32 / ROWS_PER_PASS; ++p) {
+    const int r = p * ROWS_PER_PASS + er;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(patch + r * S::EPI_PITCH + ec * 16);
+    const int row = m0 + wm * (TM * 32) + r;
+    const int col = n0 + wn * (TN * 32) + ec * 8;
+    if (row < M && col < N) *reinterpret_cast<u32x4*>(C + (size_t)row * N + col) = v;
   }
 }
 
@@ -204,6 +283,13 @@ __global__ void pid_map_kernel(int grid_m, int grid_n, int num_xcd, int group_m,
   swz_decode_tile(w, grid_m, grid_n, num_xcd, group_m, mode, &pm, &pn);
   tile[w] = pm * grid_n + pn;
   if (xcc != nullptr) xcc[w] = (int32_t)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11));
+}
+
+// Plain streaming copy of n 16-byte words (reads n*16 bytes, writes n*16 bytes): a kernel of
+// known HBM traffic against which profiler byte counters are scaled.
+__global__ __launch_bounds__(256) void copy16_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
 }  // namespace swz

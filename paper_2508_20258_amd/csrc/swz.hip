@@ -150,6 +150,17 @@ int swz_pid_map_device(int grid_m, int grid_n, int num_xcd, int group_m, int mod
   return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
 }
 
+int swz_copy_bytes(const void* src, void* dst, int64_t bytes, hipStream_t stream) {
+  if (src == nullptr || dst == nullptr || bytes < 16) return SWZ_ERR_INVALID_ARG;
+  if ((bytes & 15) || ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15)) return SWZ_ERR_UNSUPPORTED;
+  const int64_t n = bytes / 16;
+  const int64_t want = (n + 255) / 256;
+  const unsigned blocks = (unsigned)(want < 8192 ? want : 8192);
+  hipLaunchKernelGGL(swz::copy16_kernel, dim3(blocks), dim3(256), 0, stream, static_cast<const swz::u32x4*>(src),
+                     static_cast<swz::u32x4*>(dst), n);
+  return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
+}
+
 int swz_gemm_plan(int64_t M, int64_t N, int64_t K, const swz_params* params, swz_params* resolved, int* grid_m,
                   int* grid_n) {
   return resolve_plan(M, N, K, params, resolved, grid_m, grid_n);

@@ -1,0 +1,134 @@
+"""Profiling harness for the swizzled GEMM: the program that runs under rocprofv3, and the
+reader that turns rocprofv3's CSV output into the summaries kept with the measurements.
+
+    python -m paper_2508_20258_amd.harness run --workload cfg2_4096 --mode xcd_groupm --launches 10
+    python -m paper_2508_20258_amd.harness copy --mib 1024 --launches 3
+    python -m paper_2508_20258_amd.harness summarize <rocprofv3 output dir>
+
+`run` launches one mapping mode of one workload a fixed number of times, so that every GEMM
+dispatch in the trace belongs to that (workload, mode).  `copy` launches the plain copy kernel
+of known HBM traffic, against which FETCH_SIZE / WRITE_SIZE are scaled.  `summarize` prints,
+per kernel, the dispatch count, average duration, and the average of every counter found.
+The metric the paper ranks remaps by is the L2 hit rate (SwizzlePerf, Methodology step 2 and
+4): here  TCC_HIT / (TCC_HIT + TCC_MISS), from the summed TCC counters.
+"""
+from __future__ import annotations
+
+import argparse
+import csv
+import glob
+import os
+import sys
+from collections import defaultdict
+
+
+def _inputs(workload):
+    import numpy as np
+    import torch
+
+    import seeded_inputs as si
+    a_bits, b_bits = si.config_inputs(workload)
+    a = torch.from_numpy(a_bits.view(np.int16)).cuda().view(torch.bfloat16)
+    b = torch.from_numpy(b_bits.view(np.int16)).cuda().view(torch.bfloat16)
+    return a, b
+
+
+def cmd_run(args):
+    import torch
+
+    import paper_2508_20258_amd as swz
+    a, b = _inputs(args.workload)
+    c = torch.empty((a.shape[0], b.shape[1]), dtype=torch.bfloat16, device="cuda")
+    params = {}
+    if args.tile:
+        params.update(bm=args.tile, bn=args.tile)
+    if args.group_m:
+        params.update(group_m=args.group_m)
+    for _ in range(args.launches):
+        swz.gemm(a, b, c, mode=swz.MODES[args.mode], **params)
+    torch.cuda.synchronize()
+    print(f"ran {args.launches} launches of {args.workload} mode {args.mode}", flush=True)
+
+
+def cmd_copy(args):
+    import torch
+
+    import paper_2508_20258_amd as swz
+    n = args.mib << 20
+    src = torch.ones(n, dtype=torch.uint8, device="cuda")
+    dst = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    for _ in range(args.launches):
+        swz.copy_bytes(src, dst)
+    torch.cuda.synchronize()
+    print(f"ran {args.launches} copies of {args.mib} MiB (reads {n} B, writes {n} B each)", flush=True)
+
+
+def _rows(path):
+    with open(path, newline="") as f:
+        yield from csv.DictReader(f)
+
+
+def summarize(directory, kernel_filter=None):
+    """Returns {kernel name: {"n": dispatches, "avg_ns": ..., "counters": {name: avg per dispatch}}}."""
+    out = defaultdict(lambda: {"n": 0, "total_ns": 0, "counters": defaultdict(float), "counter_n": defaultdict(int)})
+    for path in glob.glob(os.path.join(directory, "**", "*kernel_trace.csv"), recursive=True):
+        for r in _rows(path):
+            k = r["Kernel_Name"]
+            out[k]["n"] += 1
+            out[k]["total_ns"] += int(r["End_Timestamp"]) - int(r["Start_Timestamp"])
+    for path in glob.glob(os.path.join(directory, "**", "*counter_collection.csv"), recursive=True):
+        per_dispatch = defaultdict(float)
+        for r in _rows(path):
+            per_dispatch[(r["Kernel_Name"], r["Dispatch_Id"], r["Counter_Name"])] += float(r["Counter_Value"])
+        for (k, _, cname), v in per_dispatch.items():
+            out[k]["counters"][cname] += v
+            out[k]["counter_n"][cname] += 1
+    res = {}
+    for k, d in out.items():
+        if kernel_filter and kernel_filter not in k:
+            continue
+        res[k] = {"n": d["n"], "avg_ns": d["total_ns"] / d["n"] if d["n"] else None,
+                  "counters": {c: d["counters"][c] / d["counter_n"][c] for c in d["counters"]}}
+    return res
+
+
+def cmd_summarize(args):
+    res = summarize(args.dir, args.kernel)
+    for k, d in sorted(res.items()):
+        short = k if len(k) < 100 else k[:97] + "..."
+        print(f"kernel: {short}")
+        if d["n"]:
+            print(f"  dispatches {d['n']}  avg duration {d['avg_ns'] / 1e3:.2f} us")
+        c = d["counters"]
+        for name in sorted(c):
+            print(f"  {name:34s} {c[name]:.6g}   (average per dispatch)")
+        if "TCC_HIT_sum" in c and "TCC_MISS_sum" in c and c["TCC_HIT_sum"] + c["TCC_MISS_sum"] > 0:
+            print(f"  L2 hit rate = TCC_HIT/(TCC_HIT+TCC_MISS) = {100 * c['TCC_HIT_sum'] / (c['TCC_HIT_sum'] + c['TCC_MISS_sum']):.2f} %")
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser(prog="harness")
+    sub = ap.add_subparsers(dest="cmd", required=True)
+    r = sub.add_parser("run")
+    r.add_argument("--workload", default="cfg2_4096")
+    r.add_argument("--mode", default="xcd_groupm", choices=["rr", "xcd", "xcd_groupm", "groupm"])
+    r.add_argument("--launches", type=int, default=10)
+    r.add_argument("--tile", type=int, default=0)
+    r.add_argument("--group-m", type=int, default=0)
+    r.set_defaults(fn=cmd_run)
+    c = sub.add_parser("copy")
+    c.add_argument("--mib", type=int, default=1024)
+    c.add_argument("--launches", type=int, default=3)
+    c.set_defaults(fn=cmd_copy)
+    s = sub.add_parser("summarize")
+    s.add_argument("dir")
+    s.add_argument("--kernel", default=None)
+    s.set_defaults(fn=cmd_summarize)
+    args = ap.parse_args(argv)
+    args.fn(args)
+
+
+if __name__ == "__main__":
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    main()
