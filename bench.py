@@ -1,13 +1,15 @@
 """Benchmark of the swizzled bf16 GEMM on one MI355X.
 
 One "step" is one whole pass of the hot path: a single swz_gemm launch (PID remap, raster
-decode, staging, MFMA loop, epilogue) over the 4096^3 workload with inputs resident in HBM.
-Prints ONE JSON line.  `value` is the swizzled (XCD renumbering + grouped-M) throughput; the
-round-robin and XCD-only figures measured in the same run are reported beside it.
+decode, global->LDS staging, MFMA loop, epilogue) over the 4096^3 workload, inputs resident
+in HBM.  Prints ONE JSON line.  `value` is the throughput of the swizzled mapping (XCD
+renumbering + grouped-M raster); the round-robin and XCD-only mappings, timed the same way in
+the same run, are reported beside it, as is the 8192^3 workload.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -17,11 +19,28 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA, published
+PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA, published (256 CUs x 4 SIMDs x 1024 flop/clk x 2.4 GHz)
+
+# HBM/fabric bytes per launch of the swizzled kernel from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE (KiB per dispatch), each scaled by what the same counter reads for the library's
+# plain 1 GiB copy kernel (FETCH_SIZE reads 0.5x the bytes copied, WRITE_SIZE 1.0x).  Valid only
+# for the kernel source whose hash is recorded here; any other kernel reports null.
+TRAFFIC = {
+    "kernel_sha256": "",
+    "cfg2_4096": {"xcd_groupm": None},
+}
+
+
+def kernel_hash() -> str:
+    h = hashlib.sha256()
+    for name in ("gemm_kernel.h", "pid_decode.h"):
+        with open(os.path.join(ROOT, "paper_2508_20258_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
 
 
 def time_mode(swz, torch, a, b, c, mode, steps, warmup):
-    """Average launch duration in ms, from events on the stream the kernel is launched on."""
+    """Average launch duration in ms: events recorded on the stream the kernel is launched on."""
     stream = torch.cuda.current_stream()
     for _ in range(warmup):
         swz.gemm(a, b, c, mode=mode, stream=stream)
@@ -38,18 +57,22 @@ def time_mode(swz, torch, a, b, c, mode, steps, warmup):
     return start.elapsed_time(stop) / steps, wall_ms / steps
 
 
-def cpu_baseline(si, a_bits, b_bits, rows):
+def to_device(torch, np, bits):
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def cpu_baseline(a_bits, b_bits, rows):
     """The oracle as it stands, on the host cores, on the first `rows` rows of the same workload."""
     from oracle import gemm_ref
     threads = gemm_ref.num_threads()
-    sub = a_bits[:rows]
-    gemm_ref.gemm(sub[:8], b_bits)                       # page everything in
+    gemm_ref.gemm(a_bits[:8], b_bits)                       # page everything in
     t0 = time.perf_counter()
-    gemm_ref.gemm(sub, b_bits)
+    gemm_ref.gemm(a_bits[:rows], b_bits)
     dt = time.perf_counter() - t0
     K, N = b_bits.shape
+    what = "the whole workload" if rows == a_bits.shape[0] else f"rows 0..{rows - 1} of A against all of B"
     return dict(value=2.0 * rows * N * K / dt / 1e12, unit="TFLOP/s", cores=threads, kind="oracle",
-                sample=f"rows 0..{rows - 1} of the same A against all of B ({rows}x{N}x{K}), fp64 triple loop, {dt:.1f} s")
+                sample=f"{what} ({rows}x{N}x{K}), fp64 triple loop with OpenMP over rows, {dt:.1f} s")
 
 
 def main():
@@ -59,7 +82,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg2_4096")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=768)
+    ap.add_argument("--no-extras", action="store_true", help="skip the 8192^3 workload and the vendor-BLAS context line")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="rows of A the oracle is timed on (0 = all)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this path uses no second device (run with --gpus 1)")
@@ -75,19 +99,26 @@ def main():
     cfg = si.CONFIGS[args.workload]
     M, N, K = cfg["M"], cfg["N"], cfg["K"]
     a_bits, b_bits = si.config_inputs(args.workload)
-    a = torch.from_numpy(a_bits.view(np.int16)).cuda().view(torch.bfloat16)
-    b = torch.from_numpy(b_bits.view(np.int16)).cuda().view(torch.bfloat16)
+    a, b = to_device(torch, np, a_bits), to_device(torch, np, b_bits)
     c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
     plan = swz.gemm_plan(M, N, K)
     flops = 2.0 * M * N * K
 
+    def pct(t):
+        return 100.0 * t / PEAK_BF16_TFLOPS
+
     per_mode = {}
     for name in ("rr", "xcd", "xcd_groupm"):
         ms, _ = time_mode(swz, torch, a, b, c, swz.MODES[name], max(args.steps // 4, 1), args.warmup)
-        per_mode[name] = dict(ms=ms, tflops=flops / ms / 1e9)
+        per_mode[name] = dict(ms=ms, tflops=flops / ms / 1e9, pct_mfma_peak=pct(flops / ms / 1e9))
     # the headline run: exactly `steps` timed launches of the swizzled kernel
     ms, wall_ms = time_mode(swz, torch, a, b, c, swz.MODE_XCD_GROUPM, args.steps, args.warmup)
     tflops = flops / ms / 1e9
+
+    traffic = None
+    rec = TRAFFIC.get(args.workload, {}).get("xcd_groupm")
+    if rec is not None and TRAFFIC["kernel_sha256"] == kernel_hash():
+        traffic = rec
 
     out = {
         "metric": "bf16 GEMM TFLOP/s + % MFMA peak + L2 hit rate, swizzled vs round-robin PID",
@@ -97,16 +128,43 @@ def main():
         "config": {"workload": f"{args.workload}: M={M} N={N} K={K}, tile {plan['bm']}x{plan['bn']}x{plan['bk']}, "
                                f"grid {plan['grid_m']}x{plan['grid_n']}, num_xcd {plan['num_xcd']}, group_m {plan['group_m']}",
                    "mode": "xcd_groupm"},
-        "pct_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
+        "pct_mfma_peak": pct(tflops),
         "wall_ms_per_step": wall_ms,
-        "modes": {k: {"ms": v["ms"], "tflops": v["tflops"], "pct_mfma_peak": 100.0 * v["tflops"] / PEAK_BF16_TFLOPS}
-                  for k, v in per_mode.items()},
+        "modes": per_mode,
         "swizzled_over_rr": per_mode["xcd_groupm"]["tflops"] / per_mode["rr"]["tflops"],
+        "l2_hit_rate": "not measurable inside this process; rocprofv3 TCC_HIT/TCC_MISS summaries per workload and mode are under profiles/",
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": tflops / PEAK_BF16_TFLOPS, "traffic": None},
+                     "frac": tflops / PEAK_BF16_TFLOPS, "traffic": traffic},
     }
+
+    if not args.no_extras:
+        # context, not the headline: what the vendor BLAS behind torch.matmul does on the same bits
+        for _ in range(10):
+            torch.matmul(a, b, out=c)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(50):
+            torch.matmul(a, b, out=c)
+        e1.record()
+        torch.cuda.synchronize()
+        out["context_vendor_blas_tflops"] = flops / (e0.elapsed_time(e1) / 50) / 1e9
+        # the large square workload, same launch path
+        big = "cfg3_8192"
+        bc = si.CONFIGS[big]
+        a3b, b3b = si.config_inputs(big)
+        a3, b3 = to_device(torch, np, a3b), to_device(torch, np, b3b)
+        c3 = torch.empty((bc["M"], bc["N"]), dtype=torch.bfloat16, device="cuda")
+        f3 = 2.0 * bc["M"] * bc["N"] * bc["K"]
+        extra = {}
+        for name in ("rr", "xcd", "xcd_groupm"):
+            m3, _ = time_mode(swz, torch, a3, b3, c3, swz.MODES[name], 30, 5)
+            extra[name] = dict(ms=m3, tflops=f3 / m3 / 1e9, pct_mfma_peak=pct(f3 / m3 / 1e9))
+        out["other_workloads"] = {big: extra}
+        del a3, b3, c3
+
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(si, a_bits, b_bits, min(args.cpu_rows, M))
+        out["cpu_baseline"] = cpu_baseline(a_bits, b_bits, args.cpu_rows or M)
     print(json.dumps(out), flush=True)
 
 

@@ -46,7 +46,7 @@ typedef enum { SWZ_DTYPE_BF16 = 0 } swz_dtype; /* A, B, C bfloat16; accumulation
 typedef struct {
   int32_t bm;      /* tile rows:    128 or 256 */
   int32_t bn;      /* tile columns: 128 or 256 (bm == bn) */
-  int32_t bk;      /* K step: 64 */
+  int32_t bk;      /* K panel per tile step: 64 (the kernel streams it as two 32-wide halves) */
   int32_t group_m; /* tile rows per band of the grouped raster (default 4) */
   int32_t num_xcd; /* XCD count assumed by the renumbering (default: detected; 8 on an unpartitioned MI355X) */
 } swz_params;

@@ -5,10 +5,14 @@
 // hardware workgroup id into a tile (pid_decode.h); nothing after that depends on the
 // mapping mode, so every mode produces the same bits.
 //
-// Staging.  Per K step of 64 the workgroup needs an A tile (BM x 64) and a B tile (64 x BN).
-// They are copied global -> LDS by the memory pipeline itself (global_load_lds_dwordx4: each
-// lane's 16 bytes land at  M0 base + lane*16, no VGPRs involved), two stages deep, so the
-// loads of step t+1 are in flight while the MFMAs of step t run.  A lane cannot choose where
+// Staging.  Per K step of BK (32 or 64) the workgroup needs an A tile (BM x BK) and a B tile
+// (BK x BN).  They are copied global -> LDS by the memory pipeline itself
+// (global_load_lds_dwordx4: each lane's 16 bytes land at  M0 base + lane*16, no VGPRs
+// involved) into a ring of STAGES buffers, so the loads of steps t+1 .. t+STAGES-1 are in
+// flight while the MFMAs of step t run.  A CU's vector memory path moves 64 bytes per clock,
+// so a 256x256x64 step (64 KB) needs >= 1024 clocks of transfer on top of the L2/HBM latency,
+// against 2048 clocks of MFMA work: one step of look-ahead is not enough, several shorter
+// steps are.  A lane cannot choose where
 // its bytes land, only what it fetches, so the XOR swizzle of the LDS layout is applied on the
 // global-address side: the lane that owns slot p of a row fetches chunk p ^ key(row).
 // Out-of-range chunks (rows >= M, columns >= N, k >= K) are fetched from a 16-byte block of
@@ -29,15 +33,18 @@
 // Main loop.  Fragments are double buffered in registers: while the MFMAs of k-block kk run,
 // the LDS reads of k-block kk+1 are issued.  The workgroup barrier of a K step sits before
 // its last k-block: by then every wave has issued all its reads of the current stage, so the
-// stage can be refilled right after the barrier, and the reads of the next stage's first
-// k-block overlap the last MFMAs.
+// stage can be refilled right after the barrier (with step t+STAGES), and the reads of the
+// next stage's first k-block overlap the last MFMAs.  Steps past the end of K are fetched as
+// zeros into stages nobody reads, which keeps the loop free of tail cases: before each
+// barrier exactly STAGES-1 steps are outstanding and the wave waits until only STAGES-2 are.
 //
 // Epilogue.  Each wave converts its accumulators to bf16 (nearest even), writes them to a
 // wave-private LDS patch and reads them back row-wise, so that global stores are 16 bytes
 // per lane and cover whole 128-byte lines.
 //
 // LDS layouts (16-byte chunks, XOR-swizzled so that the read patterns spread over banks):
-//   A: row r at byte r*128, chunk c (8 k-values) stored in slot c ^ ((r ^ (r>>3)) & 7)
+//   A, BK=64: row r at byte r*128, chunk c (8 k-values) stored in slot c ^ ((r ^ (r>>3)) & 7)
+//   A, BK=32: row r at byte r*64,  chunk c stored in slot c ^ ((r>>2) & 3)
 //   B: row k at byte k*BN*2, chunk c (8 columns) stored in slot c ^ ((k & 3) << 2)
 #pragma once
 
@@ -56,37 +63,53 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
-constexpr int kBK = 64;
-constexpr int kKK = kBK / 16;  // MFMA k-blocks per K step
 
 // Source of every out-of-range 16-byte chunk.
 __device__ const u32x4 kZeroChunk = {0u, 0u, 0u, 0u};
 
-template <int BM_, int BN_, int WM_, int WN_>
+template <int BM_, int BN_, int BK_, int STAGES_, int WM_, int WN_>
 struct GemmShape {
-  static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_, WM = WM_, WN = WN_;
+  static constexpr int KK = BK / 16;               // MFMA k-blocks per K step
   static constexpr int NW = WM * WN;               // waves per workgroup
   static constexpr int NT = NW * 64;               // threads per workgroup
   static constexpr int TM = BM / WM / 32;          // 32x32 blocks per wave, rows
   static constexpr int TN = BN / WN / 32;          // 32x32 blocks per wave, columns
-  static constexpr int A_BYTES = BM * kBK * 2;
-  static constexpr int B_BYTES = kBK * BN * 2;
+  static constexpr int A_BYTES = BM * BK * 2;
+  static constexpr int B_BYTES = BK * BN * 2;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+  static constexpr int A_ROW_CHUNKS = BK / 8;      // 16-byte chunks per A row
   static constexpr int B_ROW_CHUNKS = BN / 8;      // 16-byte chunks per B row
-  static constexpr int A_LOADS = BM * 8 / NT;      // 16-byte chunks each thread moves per step
-  static constexpr int B_LOADS = kBK * B_ROW_CHUNKS / NT;
+  static constexpr int A_LOADS = BM * A_ROW_CHUNKS / NT;   // 16-byte chunks each thread moves per step
+  static constexpr int B_LOADS = BK * B_ROW_CHUNKS / NT;
+  static constexpr int LOADS = A_LOADS + B_LOADS;
   // epilogue patch of one wave: (TM*32) rows of (TN*32) bf16, row pitch padded by 16 bytes
   static constexpr int EPI_PITCH = TN * 32 * 2 + 16;
   static constexpr int EPI_WAVE_BYTES = TM * 32 * EPI_PITCH;
   static constexpr int EPI_BYTES = NW * EPI_WAVE_BYTES;
-  static constexpr int LDS_BYTES = 2 * STAGE_BYTES > EPI_BYTES ? 2 * STAGE_BYTES : EPI_BYTES;
+  static constexpr int LDS_BYTES = STAGES * STAGE_BYTES > EPI_BYTES ? STAGES * STAGE_BYTES : EPI_BYTES;
+  static_assert(BK == 32 || BK == 64, "K step");
+  static_assert(STAGES >= 2 && (STAGES - 1) * LOADS < 64, "ring depth must fit the vmcnt counter");
   static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "wave tiling");
-  static_assert((BM * 8) % NT == 0 && (kBK * B_ROW_CHUNKS) % NT == 0, "load tiling");
+  static_assert((BM * A_ROW_CHUNKS) % NT == 0 && (BK * B_ROW_CHUNKS) % NT == 0, "load tiling");
   static_assert(TN * 32 * 2 / 16 <= 64 && 64 % (TN * 32 * 2 / 16) == 0, "epilogue row must divide a wave");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS per workgroup");
 };
 
+template <int BK>
+__device__ __forceinline__ int a_slot(int row, int chunk) {
+  return BK == 64 ? (chunk ^ ((row ^ (row >> 3)) & 7)) : (chunk ^ ((row >> 2) & 3));
+}
+
+template <int BK>
 __device__ __forceinline__ int a_lds_off(int row, int chunk) {
-  return row * 128 + ((chunk ^ ((row ^ (row >> 3)) & 7)) << 4);
+  return row * (BK * 2) + (a_slot<BK>(row, chunk) << 4);
+}
+
+// s_waitcnt that waits only for the vector-memory counter to drop to n.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | 0x0070 | 0x0F00 | ((N >> 4) << 14));
 }
 
 template <int BN>
@@ -107,17 +130,18 @@ __device__ __forceinline__ void load_to_lds(const void* gptr, unsigned char* lds
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory", "m0");
 }
 
-template <class S>
+// MODE is a template parameter so that each mapping shows up under its own kernel name in
+// profiler traces; only the decode below depends on it.
+template <class S, int MODE>
 __global__ __launch_bounds__(S::NT) void gemm_bf16_kernel(const uint16_t* __restrict__ A,
                                                           const uint16_t* __restrict__ B,
                                                           uint16_t* __restrict__ C, int M, int N, int K,
-                                                          int grid_m, int grid_n, int num_xcd, int group_m,
-                                                          int mode) {
-  constexpr int BM = S::BM, BN = S::BN, TM = S::TM, TN = S::TN;
+                                                          int grid_m, int grid_n, int num_xcd, int group_m) {
+  constexpr int BM = S::BM, BN = S::BN, BK = S::BK, KK = S::KK, TM = S::TM, TN = S::TN, STAGES = S::STAGES;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
   int pm, pn;
-  swz_decode_tile((int)blockIdx.x, grid_m, grid_n, num_xcd, group_m, mode, &pm, &pn);
+  swz_decode_tile((int)blockIdx.x, grid_m, grid_n, num_xcd, group_m, MODE, &pm, &pn);
   const int m0 = pm * BM;
   const int n0 = pn * BN;
 
@@ -136,8 +160,8 @@ __global__ __launch_bounds__(S::NT) void gemm_bf16_kernel(const uint16_t* __rest
 #pragma unroll
   for (int i = 0; i < S::A_LOADS; ++i) {
     const int q = (wave * S::A_LOADS + i) * 64 + lane;
-    const int row = q >> 3, slot = q & 7;
-    const int c = slot ^ ((row ^ (row >> 3)) & 7);
+    const int row = q / S::A_ROW_CHUNKS, slot = q % S::A_ROW_CHUNKS;
+    const int c = a_slot<BK>(row, slot);       // XOR with a key is its own inverse
     a_ok[i] = (m0 + row) < M;
     a_k[i] = c * 8;
     a_src[i] = reinterpret_cast<const unsigned char*>(A + (size_t)(a_ok[i] ? m0 + row : 0) * K + c * 8);
@@ -151,21 +175,20 @@ __global__ __launch_bounds__(S::NT) void gemm_bf16_kernel(const uint16_t* __rest
     b_k[i] = krow;
     b_src[i] = reinterpret_cast<const unsigned char*>(B + (size_t)krow * N + (b_ok[i] ? n0 + c * 8 : 0));
   }
-  const size_t a_step = (size_t)kBK * 2;          // bytes per K step along a row of A
-  const size_t b_step = (size_t)kBK * N * 2;      // bytes per K step down the rows of B
+  const size_t a_step = (size_t)BK * 2;           // bytes per K step along a row of A
+  const size_t b_step = (size_t)BK * N * 2;       // bytes per K step down the rows of B
   const unsigned char* zero = reinterpret_cast<const unsigned char*>(&kZeroChunk);
 
-  auto issue_loads = [&](int kt, int stage) {
+  // Load number idx (0 .. LOADS-1) of K step kt into `stage`; A and B loads alternate.
+  auto issue_load = [&](int kt, int stage, int idx) {
     unsigned char* sA = smem + stage * S::STAGE_BYTES;
     unsigned char* sB = sA + S::A_BYTES;
-    const int k0 = kt * kBK;
-#pragma unroll
-    for (int i = 0; i < S::A_LOADS; ++i) {
+    const int k0 = kt * BK;
+    const int i = idx >> 1;
+    if ((idx & 1) == 0) {
       const bool ok = a_ok[i] && (k0 + a_k[i] < K);
       load_to_lds(ok ? a_src[i] + kt * a_step : zero, sA + (wave * S::A_LOADS + i) * 1024);
-    }
-#pragma unroll
-    for (int i = 0; i < S::B_LOADS; ++i) {
+    } else {
       const bool ok = b_ok[i] && (k0 + b_k[i] < K);
       load_to_lds(ok ? b_src[i] + kt * b_step : zero, sB + (wave * S::B_LOADS + i) * 1024);
     }
@@ -185,63 +208,93 @@ __global__ __launch_bounds__(S::NT) void gemm_bf16_kernel(const uint16_t* __rest
   const int b_krow0 = 8 * (lane >> 5) + ((lane & 15) >> 2); // + 16*kk (+4 for the upper half)
   const int b_col0 = wn * (TN * 32) + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // + 32*bj
 
-  bf16x8 af[2][TM], bfr[2][TN];
-  auto read_frags = [&](int buf, int stage, int kk) {
+  // Fragment registers, double buffered over k-blocks.  A B fragment is two 8-byte halves.
+  bf16x8 af[2][TM];
+  s16x4 bq[2][TN][2];
+  // The d-th LDS read of a k-block (ND of them), ordered so that the operands of the first
+  // MFMAs are requested first: (B_j lower, B_j upper, A_j) for j < min(TM,TN), then the rest.
+  constexpr int NM = TM * TN;             // MFMAs per k-block
+  constexpr int ND = TM + 2 * TN;         // LDS reads per k-block
+  constexpr int NPAIR = TM < TN ? TM : TN;
+  auto read_a = [&](int buf, const unsigned char* sA, int kk, int bi) {
+    af[buf][bi] = *reinterpret_cast<const bf16x8*>(sA + a_lds_off<BK>(a_row0 + 32 * bi, a_kc0 + 2 * kk));
+  };
+  auto read_b = [&](int buf, const unsigned char* sB, int kk, int bj, int half) {
+    const int col = b_col0 + 32 * bj;
+    const int kr = b_krow0 + 16 * kk + 4 * half;
+    bq[buf][bj][half] = lds_read_tr16(sB + b_lds_off<BN>(kr, col >> 3) + (col & 7) * 2);
+  };
+  auto lds_read = [&](int buf, int stage, int kk, int d) {
     const unsigned char* sA = smem + stage * S::STAGE_BYTES;
     const unsigned char* sB = sA + S::A_BYTES;
-#pragma unroll
-    for (int bi = 0; bi < TM; ++bi)
-      af[buf][bi] = *reinterpret_cast<const bf16x8*>(sA + a_lds_off(a_row0 + 32 * bi, a_kc0 + 2 * kk));
-#pragma unroll
-    for (int bj = 0; bj < TN; ++bj) {
-      const int col = b_col0 + 32 * bj;
-      const int kr = b_krow0 + 16 * kk;
-      const s16x4 lo = lds_read_tr16(sB + b_lds_off<BN>(kr, col >> 3) + (col & 7) * 2);
-      const s16x4 hi = lds_read_tr16(sB + b_lds_off<BN>(kr + 4, col >> 3) + (col & 7) * 2);
-      bfr[buf][bj] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    if (d < 3 * NPAIR) {
+      const int j = d / 3, r = d % 3;
+      if (r < 2) read_b(buf, sB, kk, j, r); else read_a(buf, sA, kk, j);
+    } else if (TN > TM) {
+      const int e = d - 3 * NPAIR;
+      read_b(buf, sB, kk, NPAIR + e / 2, e % 2);
+    } else {
+      read_a(buf, sA, kk, NPAIR + (d - 3 * NPAIR));
     }
   };
-  auto mfmas = [&](int buf) {
-#pragma unroll
-    for (int bi = 0; bi < TM; ++bi)
-#pragma unroll
-      for (int bj = 0; bj < TN; ++bj)
-        acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[buf][bj], af[buf][bi], acc[bi][bj], 0, 0, 0);
+  auto mfma = [&](int buf, int i) {
+    const int bi = i / TN, bj = i % TN;
+    const bf16x8 b = __builtin_bit_cast(bf16x8, __builtin_shufflevector(bq[buf][bj][0], bq[buf][bj][1], 0, 1, 2, 3, 4, 5, 6, 7));
+    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, af[buf][bi], acc[bi][bj], 0, 0, 0);
   };
-  // Ask the scheduler to alternate one MFMA with one LDS read over a k-block.
-  auto interleave = [&]() {
+
+  // One k-block, issued as NM slots.  Slot i = MFMA i of the fragments in `cur`, then its share
+  // of the LDS reads that fill the other fragment buffer from (rd_stage, rd_kk), then, in the
+  // middle of every (NM/LPK)-th run of slots, one global->LDS load of K step ld_kt.  Nothing
+  // moves across slot boundaries, so memory instructions are fed to their queues at the pace
+  // of the MFMA pipe instead of in bursts that would block the (in-order) wave.
+  constexpr int LPK = S::LOADS / KK;      // global loads issued per k-block
+  constexpr int SEG = NM / LPK;
+  constexpr int RPS = 2;                  // LDS reads per slot until they run out (front-loaded: they land before the barrier)
+  static_assert(S::LOADS % KK == 0 && NM % LPK == 0 && S::A_LOADS == S::B_LOADS, "slot schedule");
+  auto kblock = [&](int cur, int rd_stage, int rd_kk, int ld_kt, int ld_stage, int ld_first) {
 #pragma unroll
-    for (int i = 0; i < TM * TN; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+    for (int i = 0; i < NM; ++i) {
+      mfma(cur, i);
+#pragma unroll
+      for (int r = 0; r < RPS; ++r)
+        if (i * RPS + r < ND) lds_read(cur ^ 1, rd_stage, rd_kk, i * RPS + r);
+      if (i % SEG == SEG / 2) issue_load(ld_kt, ld_stage, ld_first + i / SEG);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
-  const int KT = (K + kBK - 1) / kBK;
-  issue_loads(0, 0);
-  __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): stage 0 has landed (this wave's part)
-  __syncthreads();                      // ... and everybody else's
-  if (KT > 1) issue_loads(1, 1);
-  read_frags(0, 0, 0);
+  // Refill r (issued around barrier r) brings K step r+STAGES into stage r%STAGES: its first
+  // LPK loads go out in the k-block after the barrier, the others in the following k-blocks.
+  const int KT = (K + BK - 1) / BK;
+#pragma unroll
+  for (int t = 0; t < STAGES - 1; ++t)
+#pragma unroll
+    for (int l = 0; l < S::LOADS; ++l) issue_load(t, t, l);              // steps past K arrive as zeros
+#pragma unroll
+  for (int l = 0; l < LPK; ++l) issue_load(STAGES - 1, STAGES - 1, l);   // "refill -1", first part
+  wait_vmcnt<(STAGES - 2) * S::LOADS + LPK>();                            // step 0 has landed (this wave's part)
+  __syncthreads();                                                        // ... and everybody else's
+#pragma unroll
+  for (int d = 0; d < ND; ++d) lds_read(0, 0, 0, d);
 
+  int stage = 0;                       // stage of step kt
+  int prev = STAGES - 1;               // stage being refilled by the refill in progress
   for (int kt = 0; kt < KT; ++kt) {
-    const int stage = kt & 1;
 #pragma unroll
-    for (int kk = 0; kk < kKK - 1; ++kk) {
-      read_frags((kk + 1) & 1, stage, kk + 1);
-      mfmas(kk & 1);
-      interleave();
-    }
-    // Every wave has issued all its reads of `stage`; the other stage must have landed.
-    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
+    for (int kk = 0; kk < KK - 1; ++kk)
+      kblock(kk & 1, stage, kk + 1, kt - 1 + STAGES, prev, (kk + 1) * LPK);
+    // Every wave has issued all its reads of `stage`; step kt+1 must have landed.
+    wait_vmcnt<(STAGES - 2) * S::LOADS>();
     __syncthreads();
-    if (kt + 2 < KT) issue_loads(kt + 2, stage);
-    if (kt + 1 < KT) read_frags(0, stage ^ 1, 0);
-    mfmas((kKK - 1) & 1);
-    interleave();
+    const int next = (stage + 1 == STAGES) ? 0 : stage + 1;
+    kblock((KK - 1) & 1, next, 0, kt + STAGES, stage, 0);
+    prev = stage;
+    stage = next;
   }
 
   // ---- epilogue: fp32 -> bf16 (nearest even), transpose through a wave-private LDS patch ----
+  wait_vmcnt<0>();   // the zero-filled look-ahead steps have landed too
   __syncthreads();   // all waves are done with the stage buffers the patches overlay
   unsigned char* patch = smem + wave * S::EPI_WAVE_BYTES;
 #pragma unroll

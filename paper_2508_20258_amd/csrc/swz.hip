@@ -13,13 +13,14 @@ namespace {
 
 constexpr int kCusPerXcd = 32;   // gfx950: 8 XCDs x 32 CUs
 constexpr int kMaxDevices = 64;
+constexpr int kDefaultBK = 64;  // K panel of a tile step; the kernel moves it as two 32-wide halves (ring of 4)
 
 struct DeviceFacts {
   bool known = false;
   int num_xcd = 0, cus = 0, l2_bytes = 0, lds_bytes = 0;
 };
 DeviceFacts g_facts[kMaxDevices];
-bool g_attr_set[kMaxDevices][2];
+bool g_attr_set[kMaxDevices][2][4];
 std::mutex g_mu;
 
 int query_device(DeviceFacts* out) {
@@ -53,25 +54,37 @@ int check_map_args(int grid_m, int grid_n, int num_xcd, int* group_m, int mode) 
   return SWZ_OK;
 }
 
-template <class S>
-int launch_gemm(const void* A, const void* B, void* C, int M, int N, int K, int grid_m, int grid_n,
-                int num_xcd, int group_m, int mode, hipStream_t stream, int slot) {
-  auto kernel = swz::gemm_bf16_kernel<S>;
+template <class S, int MODE>
+int launch_gemm_mode(const void* A, const void* B, void* C, int M, int N, int K, int grid_m, int grid_n,
+                     int num_xcd, int group_m, hipStream_t stream, int slot) {
+  auto kernel = swz::gemm_bf16_kernel<S, MODE>;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SWZ_ERR_HIP;
   {
     std::lock_guard<std::mutex> lock(g_mu);
-    if (!g_attr_set[dev][slot]) {
+    if (!g_attr_set[dev][slot][MODE]) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                               S::LDS_BYTES) != hipSuccess)
         return SWZ_ERR_HIP;
-      g_attr_set[dev][slot] = true;
+      g_attr_set[dev][slot][MODE] = true;
     }
   }
   hipLaunchKernelGGL(kernel, dim3((unsigned)(grid_m * grid_n)), dim3(S::NT), S::LDS_BYTES, stream,
                      static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(B), static_cast<uint16_t*>(C),
-                     M, N, K, grid_m, grid_n, num_xcd, group_m, mode);
+                     M, N, K, grid_m, grid_n, num_xcd, group_m);
   return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
+}
+
+template <class S>
+int launch_gemm(const void* A, const void* B, void* C, int M, int N, int K, int grid_m, int grid_n,
+                int num_xcd, int group_m, int mode, hipStream_t stream, int slot) {
+  switch (mode) {
+    case SWZ_MODE_RR: return launch_gemm_mode<S, kModeRR>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, stream, slot);
+    case SWZ_MODE_XCD: return launch_gemm_mode<S, kModeXcd>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, stream, slot);
+    case SWZ_MODE_XCD_GROUPM: return launch_gemm_mode<S, kModeXcdGroupM>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, stream, slot);
+    case SWZ_MODE_GROUPM: return launch_gemm_mode<S, kModeGroupM>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, stream, slot);
+    default: return SWZ_ERR_INVALID_ARG;
+  }
 }
 
 int resolve_plan(int64_t M, int64_t N, int64_t K, const swz_params* p, swz_params* r, int* grid_m, int* grid_n) {
@@ -84,9 +97,9 @@ int resolve_plan(int64_t M, int64_t N, int64_t K, const swz_params* p, swz_param
   if (q.bm == 0 && q.bn == 0) q.bm = q.bn = (M <= 512 && N <= 512) ? 128 : 256;
   if (q.bm == 0) q.bm = q.bn;
   if (q.bn == 0) q.bn = q.bm;
-  if (q.bk == 0) q.bk = swz::kBK;
+  if (q.bk == 0) q.bk = kDefaultBK;
   if (q.group_m == 0) q.group_m = 4;
-  if (!((q.bm == 128 && q.bn == 128) || (q.bm == 256 && q.bn == 256)) || q.bk != swz::kBK) return SWZ_ERR_UNSUPPORTED;
+  if (!((q.bm == 128 && q.bn == 128) || (q.bm == 256 && q.bn == 256)) || q.bk != kDefaultBK) return SWZ_ERR_UNSUPPORTED;
   if (q.num_xcd == 0) {
     DeviceFacts f;
     const int st = query_device(&f);
@@ -181,9 +194,9 @@ int swz_gemm_ex(const void* A, const void* B, void* C, int64_t M, int64_t N, int
   st = check_map_args(grid_m, grid_n, r.num_xcd, &group_m, mode);
   if (st != SWZ_OK) return st;
   if (r.bm == 128)
-    return launch_gemm<swz::GemmShape<128, 128, 2, 2>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
+    return launch_gemm<swz::GemmShape<128, 128, 32, 4, 2, 2>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
                                                        group_m, mode, stream, 0);
-  return launch_gemm<swz::GemmShape<256, 256, 2, 4>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
+  return launch_gemm<swz::GemmShape<256, 256, 32, 4, 2, 4>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
                                                      group_m, mode, stream, 1);
 }
 

@@ -93,7 +93,58 @@ def summarize(directory, kernel_filter=None):
     return res
 
 
+def summarize_json(directory, kernel_filter=None):
+    """Per-kernel, per-counter averages from rocprofv3 JSON output, split by XCC where a counter has that dimension.
+
+    Returns {kernel: {"n": dispatches, "counters": {name: {"total": avg per dispatch, "per_xcc": [avg, ...] or None}}}}.
+    A dispatch's records follow the order of the counter's `instances` list.
+    """
+    import json
+    out = {}
+    for path in glob.glob(os.path.join(directory, "**", "*results.json"), recursive=True):
+        with open(path) as f:
+            doc = json.load(f)
+        for tool in doc["rocprofiler-sdk-tool"]:
+            counters = {c["id"]["handle"]: c for c in tool["counters"]}
+            names = {k["kernel_id"]: k.get("formatted_kernel_name") or k.get("kernel_name") for k in tool["kernel_symbols"]}
+            for disp in tool["callback_records"].get("counter_collection", []):
+                info = disp["dispatch_data"]["dispatch_info"]
+                kname = names.get(info["kernel_id"], str(info["kernel_id"]))
+                if kernel_filter and kernel_filter not in kname:
+                    continue
+                k = out.setdefault(kname, {"n": 0, "counters": {}})
+                k["n"] += 1
+                seen = defaultdict(int)
+                for rec in disp["records"]:
+                    c = counters[rec["counter_id"]["handle"]]
+                    inst = c["instances"][seen[c["name"]]] if seen[c["name"]] < len(c["instances"]) else None
+                    seen[c["name"]] += 1
+                    slot = k["counters"].setdefault(c["name"], {"total": 0.0, "per_xcc": defaultdict(float)})
+                    slot["total"] += rec["value"]
+                    if inst is not None:
+                        for dim in inst["dimensions"]:
+                            if dim["dimension_name"] == "DIMENSION_XCC":
+                                slot["per_xcc"][dim["index"]] += rec["value"]
+    for k in out.values():
+        for slot in k["counters"].values():
+            slot["total"] /= k["n"]
+            slot["per_xcc"] = [slot["per_xcc"][i] / k["n"] for i in sorted(slot["per_xcc"])] or None
+    return out
+
+
 def cmd_summarize(args):
+    for kname, d in sorted(summarize_json(args.dir, args.kernel).items()):
+        short = kname if len(kname) < 100 else kname[:97] + "..."
+        print(f"kernel: {short}\n  dispatches with counters {d['n']}")
+        c = d["counters"]
+        for name in sorted(c):
+            print(f"  {name:34s} {c[name]['total']:.6g}   (average per dispatch)")
+        if "TCC_HIT" in c and "TCC_MISS" in c:
+            h, m = c["TCC_HIT"], c["TCC_MISS"]
+            print(f"  L2 hit rate = TCC_HIT/(TCC_HIT+TCC_MISS) = {100 * h['total'] / (h['total'] + m['total']):.2f} %")
+            if h["per_xcc"] and m["per_xcc"]:
+                rates = [100 * a / (a + b) if a + b else float('nan') for a, b in zip(h["per_xcc"], m["per_xcc"])]
+                print("  per XCD: " + " ".join(f"{r:.2f}" for r in rates) + " %")
     res = summarize(args.dir, args.kernel)
     for k, d in sorted(res.items()):
         short = k if len(k) < 100 else k[:97] + "..."
