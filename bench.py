@@ -26,8 +26,10 @@ PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA, published (256 CUs x 
 # plain 1 GiB copy kernel (FETCH_SIZE reads 0.5x the bytes copied, WRITE_SIZE 1.0x).  Valid only
 # for the kernel source whose hash is recorded here; any other kernel reports null.
 TRAFFIC = {
-    "kernel_sha256": "",
-    "cfg2_4096": {"xcd_groupm": None},
+    "kernel_sha256": "3acf4528a4e88c32cd948de457d78071afa747f09a8a588a6d5bdd2a55e4a9b1",
+    # FETCH_SIZE 98358 KiB x 2.0 + WRITE_SIZE 32768 KiB x 1.0 per dispatch (profiles/gemm_cfg2_4096.txt)
+    "cfg2_4096": {"xcd_groupm": {"fetch_bytes": 201437798, "write_bytes": 33554432, "total_bytes": 234992230,
+                                 "algorithmic_min_bytes": 100663296}},
 }
 
 
