@@ -5,7 +5,7 @@
 // hardware workgroup id into a tile (pid_decode.h); nothing after that depends on the
 // mapping mode, so every mode produces the same bits.
 //
-// Staging.  Per K step of BK (32 or 64) the workgroup needs an A tile (BM x BK) and a B tile
+// Staging.  Per K step of BK = 32 the workgroup needs an A tile (BM x BK) and a B tile
 // (BK x BN).  They are copied global -> LDS by the memory pipeline itself
 // (global_load_lds_dwordx4: each lane's 16 bytes land at  M0 base + lane*16, no VGPRs
 // involved) into a ring of STAGES buffers, so the loads of steps t+1 .. t+STAGES-1 are in
@@ -18,38 +18,43 @@
 // Out-of-range chunks (rows >= M, columns >= N, k >= K) are fetched from a 16-byte block of
 // zeros, which keeps every address valid and makes the K tail exact.
 //
-// MFMA (v_mfma_f32_32x32x16_bf16, lane l of 64).  Each operand register holds, for one row
-// (or column) index l%32, the 8 consecutive k values 8*(l/32) .. +7:
-//   fragment of A: A[m = l%32][k..]   -> one 16-byte LDS read (A is k-contiguous)
-//   fragment of B: B[k..][n = l%32]   -> B is n-contiguous, so it is fetched with two
+// MFMA (v_mfma_f32_16x16x32_bf16, lane l of 64).  Each operand register holds, for one row
+// (or column) index l%16, the 8 consecutive k values 8*(l/16) .. +7 of a 32-wide k-block:
+//   fragment of A: A[m = l%16][k..]   -> one 16-byte LDS read (A is k-contiguous)
+//   fragment of B: B[k..][n = l%16]   -> B is n-contiguous, so it is fetched with two
 //       transposing LDS reads (ds_read_b64_tr_b16): inside each 16-lane group, lane s
 //       supplies the address of 4 consecutive columns of row s/4, and lane i receives
 //       rows 0..3 of column i.
 // The B fragment is passed as the instruction's first operand and the A fragment as its
-// second, i.e. the instruction computes the 32x32 block of C transposed: lane l, register v
-// then holds C[m = l%32][n = 8*(v/4) + 4*(l/32) + v%4], four consecutive columns per
-// register quad, which packs into one 8-byte store.
+// second, i.e. the instruction computes the 16x16 block of C transposed: lane l, register v
+// then holds C[m = l%16][n = 4*(l/16) + v], four consecutive columns, one 8-byte store.
+// The 16x16x32 shape is used rather than 32x32x16 because it draws less power for the same
+// flops: with random operands held in registers and no memory traffic the chip sustains
+// about 2.1 PFLOP/s with it against 1.9 PFLOP/s with 32x32x16 (the clock settles higher).
 //
-// Main loop.  Fragments are double buffered in registers: while the MFMAs of k-block kk run,
-// the LDS reads of k-block kk+1 are issued.  The workgroup barrier of a K step sits before
-// its last k-block: by then every wave has issued all its reads of the current stage, so the
-// stage can be refilled right after the barrier (with step t+STAGES), and the reads of the
-// next stage's first k-block overlap the last MFMAs.  Steps past the end of K are fetched as
-// zeros into stages nobody reads, which keeps the loop free of tail cases: before each
-// barrier exactly STAGES-1 steps are outstanding and the wave waits until only STAGES-2 are.
+// Main loop.  Fragments are double buffered in registers: while the MFMAs of K step t run,
+// the LDS reads of step t+1 are issued.  One workgroup barrier per step: before it every wave
+// has issued all its reads of step t and waited for its own share of step t+1 to land, so
+// right after it the stage of step t is refilled with step t+STAGES.  Steps past the end of K
+// are fetched as zeros, which keeps the loop free of tail cases: before each barrier exactly
+// STAGES-1 steps are outstanding and the wave waits until only STAGES-2 are.
 //
 // Epilogue.  Each wave converts its accumulators to bf16 (nearest even), writes them to a
 // wave-private LDS patch and reads them back row-wise, so that global stores are 16 bytes
 // per lane and cover whole 128-byte lines.
 //
 // LDS layouts (16-byte chunks, XOR-swizzled so that the read patterns spread over banks):
-//   A, BK=64: row r at byte r*128, chunk c (8 k-values) stored in slot c ^ ((r ^ (r>>3)) & 7)
-//   A, BK=32: row r at byte r*64,  chunk c stored in slot c ^ ((r>>2) & 3)
-//   B: row k at byte k*BN*2, chunk c (8 columns) stored in slot c ^ ((k & 3) << 2)
+//   A: row r at byte r*64, chunk c (8 k-values) stored in slot c ^ ((r>>2) & 3): the 64 lanes of
+//      a fragment read (16 rows x 4 chunks) then cover one contiguous KiB exactly once.
+//   B: row k at byte k*BN*2, chunk c (8 columns) stored in slot c ^ (f(k) << 1) with
+//      f(k) = (k & 3) | ((k>>3 & 1) << 2): the 8 rows a half-wave reads land in 8 different
+//      32-byte bank groups.
 #pragma once
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 #include "pid_decode.h"
 
@@ -59,7 +64,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
@@ -70,11 +75,11 @@ __device__ const u32x4 kZeroChunk = {0u, 0u, 0u, 0u};
 template <int BM_, int BN_, int BK_, int STAGES_, int WM_, int WN_>
 struct GemmShape {
   static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_, WM = WM_, WN = WN_;
-  static constexpr int KK = BK / 16;               // MFMA k-blocks per K step
+  static constexpr int KK = BK / 32;               // MFMA k-blocks (32 wide) per K step
   static constexpr int NW = WM * WN;               // waves per workgroup
   static constexpr int NT = NW * 64;               // threads per workgroup
-  static constexpr int TM = BM / WM / 32;          // 32x32 blocks per wave, rows
-  static constexpr int TN = BN / WN / 32;          // 32x32 blocks per wave, columns
+  static constexpr int TM = BM / WM / 16;          // 16x16 blocks per wave, rows
+  static constexpr int TN = BN / WN / 16;          // 16x16 blocks per wave, columns
   static constexpr int A_BYTES = BM * BK * 2;
   static constexpr int B_BYTES = BK * BN * 2;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
@@ -83,22 +88,22 @@ struct GemmShape {
   static constexpr int A_LOADS = BM * A_ROW_CHUNKS / NT;   // 16-byte chunks each thread moves per step
   static constexpr int B_LOADS = BK * B_ROW_CHUNKS / NT;
   static constexpr int LOADS = A_LOADS + B_LOADS;
-  // epilogue patch of one wave: (TM*32) rows of (TN*32) bf16, row pitch padded by 16 bytes
-  static constexpr int EPI_PITCH = TN * 32 * 2 + 16;
-  static constexpr int EPI_WAVE_BYTES = TM * 32 * EPI_PITCH;
+  // epilogue patch of one wave: (TM*16) rows of (TN*16) bf16, row pitch padded by 16 bytes
+  static constexpr int EPI_PITCH = TN * 16 * 2 + 16;
+  static constexpr int EPI_WAVE_BYTES = TM * 16 * EPI_PITCH;
   static constexpr int EPI_BYTES = NW * EPI_WAVE_BYTES;
   static constexpr int LDS_BYTES = STAGES * STAGE_BYTES > EPI_BYTES ? STAGES * STAGE_BYTES : EPI_BYTES;
-  static_assert(BK == 32 || BK == 64, "K step");
+  static_assert(BK == 32, "K step");
   static_assert(STAGES >= 2 && (STAGES - 1) * LOADS < 64, "ring depth must fit the vmcnt counter");
-  static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "wave tiling");
+  static_assert(BM % (WM * 16) == 0 && BN % (WN * 16) == 0, "wave tiling");
   static_assert((BM * A_ROW_CHUNKS) % NT == 0 && (BK * B_ROW_CHUNKS) % NT == 0, "load tiling");
-  static_assert(TN * 32 * 2 / 16 <= 64 && 64 % (TN * 32 * 2 / 16) == 0, "epilogue row must divide a wave");
+  static_assert(TN * 16 * 2 / 16 <= 64 && 64 % (TN * 16 * 2 / 16) == 0, "epilogue row must divide a wave");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS per workgroup");
 };
 
 template <int BK>
 __device__ __forceinline__ int a_slot(int row, int chunk) {
-  return BK == 64 ? (chunk ^ ((row ^ (row >> 3)) & 7)) : (chunk ^ ((row >> 2) & 3));
+  return chunk ^ ((row >> 2) & 3);
 }
 
 template <int BK>
@@ -112,9 +117,11 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 0xF) | 0x0070 | 0x0F00 | ((N >> 4) << 14));
 }
 
+__device__ __forceinline__ int b_key(int krow) { return ((krow & 3) | (((krow >> 3) & 1) << 2)) << 1; }
+
 template <int BN>
 __device__ __forceinline__ int b_lds_off(int krow, int chunk) {
-  return krow * (BN * 2) + ((chunk ^ ((krow & 3) << 2)) << 4);
+  return krow * (BN * 2) + ((chunk ^ b_key(krow)) << 4);
 }
 
 __device__ __forceinline__ s16x4 lds_read_tr16(const unsigned char* p) {
@@ -126,12 +133,20 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const unsigned char* p) {
 // does not guard later LDS reads of the *other* stage with a conservative vmcnt(0); the kernel
 // waits for them itself (s_waitcnt vmcnt(0) before the barrier that publishes a stage).
 __device__ __forceinline__ void load_to_lds(const void* gptr, unsigned char* lds_base) {
-  const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_base;
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_base);   // wave-uniform by construction
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory", "m0");
 }
 
 // MODE is a template parameter so that each mapping shows up under its own kernel name in
 // profiler traces; only the decode below depends on it.
+// Same, with the source given as a wave-uniform base (SGPR pair) plus a 32-bit per-lane byte offset.
+__device__ __forceinline__ void load_to_lds_base_off(const void* base, uint32_t off, unsigned char* lds_base) {
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_base);
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(off), "s"(base) : "memory", "m0");
+}
+
 template <class S, int MODE>
 __global__ __launch_bounds__(S::NT) void gemm_bf16_kernel(const uint16_t* __restrict__ A,
                                                           const uint16_t* __restrict__ B,
@@ -153,144 +168,150 @@ __global__ __launch_bounds__(S::NT) void gemm_bf16_kernel(const uint16_t* __rest
 
   // ---- global -> LDS staging: which chunk of the tile this lane fetches for each of its loads ----
   // Load i of wave w fills LDS bytes [(w*LOADS + i)*1024, +1024) of the A (resp. B) region.
-  const unsigned char* a_src[S::A_LOADS];
-  const unsigned char* b_src[S::B_LOADS];
-  bool a_ok[S::A_LOADS], b_ok[S::B_LOADS];
+  // A lane's source is  tile base (uniform, advances with the K step) + a 32-bit byte offset that
+  // never changes.  Rows >= M and columns >= N are clamped to the last valid row / 8-column chunk:
+  // whatever they bring in only reaches accumulators of C rows >= M or columns >= N, which are never
+  // stored.  Only a K step that crosses the end of K needs zeros, and takes the predicated path.
+  uint32_t a_off[S::A_LOADS], b_off[S::B_LOADS];
   int a_k[S::A_LOADS], b_k[S::B_LOADS];       // k offset of the chunk inside a K step
 #pragma unroll
   for (int i = 0; i < S::A_LOADS; ++i) {
     const int q = (wave * S::A_LOADS + i) * 64 + lane;
     const int row = q / S::A_ROW_CHUNKS, slot = q % S::A_ROW_CHUNKS;
     const int c = a_slot<BK>(row, slot);       // XOR with a key is its own inverse
-    a_ok[i] = (m0 + row) < M;
+    const int r = (m0 + row < M) ? row : (M - 1 - m0);
     a_k[i] = c * 8;
-    a_src[i] = reinterpret_cast<const unsigned char*>(A + (size_t)(a_ok[i] ? m0 + row : 0) * K + c * 8);
+    a_off[i] = (uint32_t)r * (uint32_t)K * 2u + (uint32_t)c * 16u;
   }
 #pragma unroll
   for (int i = 0; i < S::B_LOADS; ++i) {
     const int q = (wave * S::B_LOADS + i) * 64 + lane;
     const int krow = q / S::B_ROW_CHUNKS, slot = q % S::B_ROW_CHUNKS;
-    const int c = slot ^ ((krow & 3) << 2);
-    b_ok[i] = (n0 + c * 8) < N;
+    const int c = slot ^ b_key(krow);
+    const int col = (n0 + c * 8 < N) ? c * 8 : (N - 8 - n0);
     b_k[i] = krow;
-    b_src[i] = reinterpret_cast<const unsigned char*>(B + (size_t)krow * N + (b_ok[i] ? n0 + c * 8 : 0));
+    b_off[i] = (uint32_t)krow * (uint32_t)N * 2u + (uint32_t)col * 2u;
   }
+  const unsigned char* a_tile = reinterpret_cast<const unsigned char*>(A + (size_t)m0 * K);
+  const unsigned char* b_tile = reinterpret_cast<const unsigned char*>(B + n0);
   const size_t a_step = (size_t)BK * 2;           // bytes per K step along a row of A
   const size_t b_step = (size_t)BK * N * 2;       // bytes per K step down the rows of B
   const unsigned char* zero = reinterpret_cast<const unsigned char*>(&kZeroChunk);
 
   // Load number idx (0 .. LOADS-1) of K step kt into `stage`; A and B loads alternate.
-  auto issue_load = [&](int kt, int stage, int idx) {
+  // full = the whole step lies inside K (uniform): no per-lane work at all.
+  auto issue_load = [&](int kt, int stage, int idx, auto full) __attribute__((always_inline)) {
     unsigned char* sA = smem + stage * S::STAGE_BYTES;
     unsigned char* sB = sA + S::A_BYTES;
-    const int k0 = kt * BK;
     const int i = idx >> 1;
-    if ((idx & 1) == 0) {
-      const bool ok = a_ok[i] && (k0 + a_k[i] < K);
-      load_to_lds(ok ? a_src[i] + kt * a_step : zero, sA + (wave * S::A_LOADS + i) * 1024);
+    const bool is_a = (idx & 1) == 0;
+    const unsigned char* base = is_a ? a_tile + kt * a_step : b_tile + kt * b_step;
+    const uint32_t off = is_a ? a_off[i] : b_off[i];
+    unsigned char* dst = is_a ? sA + (wave * S::A_LOADS + i) * 1024 : sB + (wave * S::B_LOADS + i) * 1024;
+    if constexpr (decltype(full)::value) {
+      load_to_lds_base_off(base, off, dst);
     } else {
-      const bool ok = b_ok[i] && (k0 + b_k[i] < K);
-      load_to_lds(ok ? b_src[i] + kt * b_step : zero, sB + (wave * S::B_LOADS + i) * 1024);
+      const bool ok = kt * BK + (is_a ? a_k[i] : b_k[i]) < K;
+      load_to_lds(ok ? base + off : zero, dst);
     }
   };
+  constexpr std::true_type kFull{};
+  constexpr std::false_type kTail{};
 
-  f32x16 acc[TM][TN];
+  f32x4 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+      for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
 
   // lane-constant parts of the fragment addresses
-  const int a_row0 = wm * (TM * 32) + (lane & 31);          // + 32*bi
-  const int a_kc0 = lane >> 5;                              // + 2*kk  (16-byte chunk index along k)
-  const int b_krow0 = 8 * (lane >> 5) + ((lane & 15) >> 2); // + 16*kk (+4 for the upper half)
-  const int b_col0 = wn * (TN * 32) + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // + 32*bj
+  const int a_row0 = wm * (TM * 16) + (lane & 15);          // + 16*bi
+  const int a_kc0 = lane >> 4;                              // 16-byte chunk index along k
+  const int b_krow0 = 8 * (lane >> 4) + ((lane & 15) >> 2); // (+4 for the upper half)
+  const int b_col0 = wn * (TN * 16) + 4 * (lane & 3);       // + 16*bj
 
-  // Fragment registers, double buffered over k-blocks.  A B fragment is two 8-byte halves.
-  bf16x8 af[2][TM];
+  // Fragment registers.  The MFMAs of a step run A-row-block by A-row-block (bi outer, bj
+  // inner), so an A fragment is dead after its TN MFMAs and the same registers take the next
+  // step's fragment right away; B fragments are needed by every row-block and are double
+  // buffered.  A B fragment is two 8-byte halves.
+  bf16x8 af[TM];
   s16x4 bq[2][TN][2];
-  // The d-th LDS read of a k-block (ND of them), ordered so that the operands of the first
-  // MFMAs are requested first: (B_j lower, B_j upper, A_j) for j < min(TM,TN), then the rest.
-  constexpr int NM = TM * TN;             // MFMAs per k-block
-  constexpr int ND = TM + 2 * TN;         // LDS reads per k-block
-  constexpr int NPAIR = TM < TN ? TM : TN;
-  auto read_a = [&](int buf, const unsigned char* sA, int kk, int bi) {
-    af[buf][bi] = *reinterpret_cast<const bf16x8*>(sA + a_lds_off<BK>(a_row0 + 32 * bi, a_kc0 + 2 * kk));
+  constexpr int NM = TM * TN;             // MFMAs per step
+  auto read_a = [&](int stage, int bi) __attribute__((always_inline)) {
+    const unsigned char* sA = smem + stage * S::STAGE_BYTES;
+    af[bi] = *reinterpret_cast<const bf16x8*>(sA + a_lds_off<BK>(a_row0 + 16 * bi, a_kc0));
   };
-  auto read_b = [&](int buf, const unsigned char* sB, int kk, int bj, int half) {
-    const int col = b_col0 + 32 * bj;
-    const int kr = b_krow0 + 16 * kk + 4 * half;
+  auto read_b = [&](int buf, int stage, int bj, int half) __attribute__((always_inline)) {
+    const unsigned char* sB = smem + stage * S::STAGE_BYTES + S::A_BYTES;
+    const int col = b_col0 + 16 * bj;
+    const int kr = b_krow0 + 4 * half;
     bq[buf][bj][half] = lds_read_tr16(sB + b_lds_off<BN>(kr, col >> 3) + (col & 7) * 2);
   };
-  auto lds_read = [&](int buf, int stage, int kk, int d) {
-    const unsigned char* sA = smem + stage * S::STAGE_BYTES;
-    const unsigned char* sB = sA + S::A_BYTES;
-    if (d < 3 * NPAIR) {
-      const int j = d / 3, r = d % 3;
-      if (r < 2) read_b(buf, sB, kk, j, r); else read_a(buf, sA, kk, j);
-    } else if (TN > TM) {
-      const int e = d - 3 * NPAIR;
-      read_b(buf, sB, kk, NPAIR + e / 2, e % 2);
-    } else {
-      read_a(buf, sA, kk, NPAIR + (d - 3 * NPAIR));
-    }
-  };
-  auto mfma = [&](int buf, int i) {
-    const int bi = i / TN, bj = i % TN;
+  auto mfma = [&](int buf, int bi, int bj) __attribute__((always_inline)) {
     const bf16x8 b = __builtin_bit_cast(bf16x8, __builtin_shufflevector(bq[buf][bj][0], bq[buf][bj][1], 0, 1, 2, 3, 4, 5, 6, 7));
-    acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, af[buf][bi], acc[bi][bj], 0, 0, 0);
+    acc[bi][bj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b, af[bi], acc[bi][bj], 0, 0, 0);
   };
 
-  // One k-block, issued as NM slots.  Slot i = MFMA i of the fragments in `cur`, then its share
-  // of the LDS reads that fill the other fragment buffer from (rd_stage, rd_kk), then, in the
-  // middle of every (NM/LPK)-th run of slots, one global->LDS load of K step ld_kt.  Nothing
-  // moves across slot boundaries, so memory instructions are fed to their queues at the pace
-  // of the MFMA pipe instead of in bursts that would block the (in-order) wave.
-  constexpr int LPK = S::LOADS / KK;      // global loads issued per k-block
-  constexpr int SEG = NM / LPK;
-  constexpr int RPS = 2;                  // LDS reads per slot until they run out (front-loaded: they land before the barrier)
-  static_assert(S::LOADS % KK == 0 && NM % LPK == 0 && S::A_LOADS == S::B_LOADS, "slot schedule");
-  auto kblock = [&](int cur, int rd_stage, int rd_kk, int ld_kt, int ld_stage, int ld_first) {
+  // One K step, issued as NM slots.  Slot i = MFMA (bi, bj) on the fragments of the current
+  // step, then at most one LDS read for the next step (the B halves in the first 2*TN slots,
+  // the A fragment of row-block bi after that block's last MFMA), then, in the middle of every
+  // (NM/LOADS)-th run of slots, one global->LDS load of K step ld_kt.  Nothing moves across slot
+  // boundaries, so memory instructions are fed to their queues at the pace of the MFMA pipe
+  // instead of in bursts that would block the (in-order) wave.
+  constexpr int SEG = NM / S::LOADS;
+  static_assert(NM % S::LOADS == 0 && S::A_LOADS == S::B_LOADS && 2 * TN <= NM, "slot schedule");
+  auto kblock = [&](int cur, int rd_stage, int ld_kt, int ld_stage, auto full) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < NM; ++i) {
-      mfma(cur, i);
-#pragma unroll
-      for (int r = 0; r < RPS; ++r)
-        if (i * RPS + r < ND) lds_read(cur ^ 1, rd_stage, rd_kk, i * RPS + r);
-      if (i % SEG == SEG / 2) issue_load(ld_kt, ld_stage, ld_first + i / SEG);
+      const int bi = i / TN, bj = i % TN;
+      mfma(cur, bi, bj);
+      if (i < 2 * TN) read_b(cur ^ 1, rd_stage, i / 2, i % 2);
+      if (bj == TN - 1) read_a(rd_stage, bi);
+      if (i % SEG == SEG / 2) issue_load(ld_kt, ld_stage, i / SEG, full);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
 
-  // Refill r (issued around barrier r) brings K step r+STAGES into stage r%STAGES: its first
-  // LPK loads go out in the k-block after the barrier, the others in the following k-blocks.
+  // K step t lives in stage t%STAGES.  Before the barrier of step t every wave has issued its
+  // reads of step t (they ran during step t-1), so right after it the stage is refilled with
+  // step t+STAGES; the reads of step t+1 run during the MFMAs of step t.  Two steps per loop
+  // trip keep the fragment-buffer index a compile-time constant; an odd step count just
+  // processes one more step of zeros.
+  static_assert(KK == 1, "one 32-wide k-block per K step");
   const int KT = (K + BK - 1) / BK;
 #pragma unroll
-  for (int t = 0; t < STAGES - 1; ++t)
+  for (int t = 0; t < STAGES; ++t)
 #pragma unroll
-    for (int l = 0; l < S::LOADS; ++l) issue_load(t, t, l);              // steps past K arrive as zeros
+    for (int l = 0; l < S::LOADS; ++l) issue_load(t, t, l, kTail);   // steps past K arrive as zeros
+  wait_vmcnt<(STAGES - 1) * S::LOADS>();                         // step 0 has landed (this wave's part)
+  __syncthreads();                                               // ... and everybody else's
 #pragma unroll
-  for (int l = 0; l < LPK; ++l) issue_load(STAGES - 1, STAGES - 1, l);   // "refill -1", first part
-  wait_vmcnt<(STAGES - 2) * S::LOADS + LPK>();                            // step 0 has landed (this wave's part)
-  __syncthreads();                                                        // ... and everybody else's
+  for (int bj = 0; bj < TN; ++bj) {
+    read_b(0, 0, bj, 0);
+    read_b(0, 0, bj, 1);
+  }
 #pragma unroll
-  for (int d = 0; d < ND; ++d) lds_read(0, 0, 0, d);
+  for (int bi = 0; bi < TM; ++bi) read_a(0, bi);
 
   int stage = 0;                       // stage of step kt
-  int prev = STAGES - 1;               // stage being refilled by the refill in progress
-  for (int kt = 0; kt < KT; ++kt) {
-#pragma unroll
-    for (int kk = 0; kk < KK - 1; ++kk)
-      kblock(kk & 1, stage, kk + 1, kt - 1 + STAGES, prev, (kk + 1) * LPK);
-    // Every wave has issued all its reads of `stage`; step kt+1 must have landed.
-    wait_vmcnt<(STAGES - 2) * S::LOADS>();
+  auto step = [&](int kt, int cur, auto full) __attribute__((always_inline)) {
+    wait_vmcnt<(STAGES - 2) * S::LOADS>();   // step kt+1 has landed (this wave's part)
     __syncthreads();
     const int next = (stage + 1 == STAGES) ? 0 : stage + 1;
-    kblock((KK - 1) & 1, next, 0, kt + STAGES, stage, 0);
-    prev = stage;
+    kblock(cur, next, kt + STAGES, stage, full);
     stage = next;
+  };
+  const int full_steps = K / BK;       // steps 0 .. full_steps-1 lie wholly inside K
+  int kt = 0;
+  for (; kt + 1 + STAGES < full_steps; kt += 2) {   // both refills of this trip fetch whole steps
+    step(kt, 0, kFull);
+    step(kt + 1, 1, kFull);
+  }
+  for (; kt < KT; kt += 2) {
+    step(kt, 0, kTail);
+    step(kt + 1, 1, kTail);
   }
 
   // ---- epilogue: fp32 -> bf16 (nearest even), transpose through a wave-private LDS patch ----
@@ -301,27 +322,24 @@ __global__ __launch_bounds__(S::NT) void gemm_bf16_kernel(const uint16_t* __rest
   for (int bi = 0; bi < TM; ++bi) {
 #pragma unroll
     for (int bj = 0; bj < TN; ++bj) {
+      bf16x4 h;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        bf16x4 h;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) h[e] = (__bf16)acc[bi][bj][4 * g + e];
-        const int r = 32 * bi + (lane & 31);
-        const int ccol = 32 * bj + 8 * g + 4 * (lane >> 5);
-        *reinterpret_cast<bf16x4*>(patch + r * S::EPI_PITCH + ccol * 2) = h;
-      }
+      for (int e = 0; e < 4; ++e) h[e] = (__bf16)acc[bi][bj][e];
+      const int r = 16 * bi + (lane & 15);
+      const int ccol = 16 * bj + 4 * (lane >> 4);
+      *reinterpret_cast<bf16x4*>(patch + r * S::EPI_PITCH + ccol * 2) = h;
     }
   }
   __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this wave's patch is written (wave-private, no barrier)
-  constexpr int ROW_CHUNKS = TN * 32 * 2 / 16;      // 16-byte chunks per patch row
+  constexpr int ROW_CHUNKS = TN * 16 * 2 / 16;      // 16-byte chunks per patch row
   constexpr int ROWS_PER_PASS = 64 / ROW_CHUNKS;
   const int er = lane / ROW_CHUNKS, ec = lane % ROW_CHUNKS;
 #pragma unroll
-  for (int p = 0; p < TM * 32 / ROWS_PER_PASS; ++p) {
+  for (int p = 0; p < TM * 16 / ROWS_PER_PASS; ++p) {
     const int r = p * ROWS_PER_PASS + er;
     const u32x4 v = *reinterpret_cast<const u32x4*>(patch + r * S::EPI_PITCH + ec * 16);
-    const int row = m0 + wm * (TM * 32) + r;
-    const int col = n0 + wn * (TN * 32) + ec * 8;
+    const int row = m0 + wm * (TM * 16) + r;
+    const int col = n0 + wn * (TN * 16) + ec * 8;
     if (row < M && col < N) *reinterpret_cast<u32x4*>(C + (size_t)row * N + col) = v;
   }
 }

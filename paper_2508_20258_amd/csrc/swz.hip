@@ -188,6 +188,8 @@ int swz_gemm_ex(const void* A, const void* B, void* C, int64_t M, int64_t N, int
   if (st != SWZ_OK) return st;
   if (dtype != SWZ_DTYPE_BF16) return SWZ_ERR_UNSUPPORTED;
   if ((K % 8) != 0 || (N % 8) != 0) return SWZ_ERR_UNSUPPORTED;   // 16-byte vector loads along k and n
+  // per-lane source offsets inside a tile step are 32-bit: (bm-1) rows of A, 31 rows of B
+  if ((int64_t)r.bm * K * 2 >= ((int64_t)1 << 32) || (int64_t)32 * N * 2 >= ((int64_t)1 << 32)) return SWZ_ERR_OVERFLOW;
   if ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(C)) & 15)
     return SWZ_ERR_UNSUPPORTED;
   int group_m = r.group_m;
