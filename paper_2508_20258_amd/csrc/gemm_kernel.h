@@ -32,12 +32,12 @@
 // flops: with random operands held in registers and no memory traffic the chip sustains
 // about 2.1 PFLOP/s with it against 1.9 PFLOP/s with 32x32x16 (the clock settles higher).
 //
-// Main loop.  Fragments are double buffered in registers: while the MFMAs of K step t run,
-// the LDS reads of step t+1 are issued.  One workgroup barrier per step: before it every wave
-// has issued all its reads of step t and waited for its own share of step t+1 to land, so
-// right after it the stage of step t is refilled with step t+STAGES.  Steps past the end of K
-// are fetched as zeros, which keeps the loop free of tail cases: before each barrier exactly
-// STAGES-1 steps are outstanding and the wave waits until only STAGES-2 are.
+// Main loop.  While the MFMAs of K step t run, the LDS reads of step t+1 and the global loads
+// of step t+STAGES-1 are issued, one memory instruction per MFMA slot.  One workgroup barrier
+// per step, with no LDS-counter wait attached (the stage that is refilled after it was consumed
+// a whole step earlier).  Steps past the end of K are fetched as zeros, which keeps the loop
+// free of tail cases: before each barrier exactly STAGES-2 steps are outstanding and the wave
+// waits until only STAGES-3 are.
 //
 // Epilogue.  Each wave converts its accumulators to bf16 (nearest even), writes them to a
 // wave-private LDS patch and reads them back row-wise, so that global stores are 16 bytes
@@ -94,7 +94,7 @@ struct GemmShape {
   static constexpr int EPI_BYTES = NW * EPI_WAVE_BYTES;
   static constexpr int LDS_BYTES = STAGES * STAGE_BYTES > EPI_BYTES ? STAGES * STAGE_BYTES : EPI_BYTES;
   static_assert(BK == 32, "K step");
-  static_assert(STAGES >= 2 && (STAGES - 1) * LOADS < 64, "ring depth must fit the vmcnt counter");
+  static_assert(STAGES >= 3 && (STAGES - 1) * LOADS < 64, "ring depth must fit the vmcnt counter");
   static_assert(BM % (WM * 16) == 0 && BN % (WN * 16) == 0, "wave tiling");
   static_assert((BM * A_ROW_CHUNKS) % NT == 0 && (BK * B_ROW_CHUNKS) % NT == 0, "load tiling");
   static_assert(TN * 16 * 2 / 16 <= 64 && 64 % (TN * 16 * 2 / 16) == 0, "epilogue row must divide a wave");
@@ -110,6 +110,10 @@ template <int BK>
 __device__ __forceinline__ int a_lds_off(int row, int chunk) {
   return row * (BK * 2) + (a_slot<BK>(row, chunk) << 4);
 }
+
+// Workgroup barrier alone: no counter waits attached (the kernel states the ones it needs), and
+// the memory clobber keeps the compiler from moving LDS accesses across it.
+__device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
 // s_waitcnt that waits only for the vector-memory counter to drop to n.
 template <int N>
@@ -274,18 +278,22 @@ __global__ __launch_bounds__(S::NT) void gemm_bf16_kernel(const uint16_t* __rest
     }
   };
 
-  // K step t lives in stage t%STAGES.  Before the barrier of step t every wave has issued its
-  // reads of step t (they ran during step t-1), so right after it the stage is refilled with
-  // step t+STAGES; the reads of step t+1 run during the MFMAs of step t.  Two steps per loop
-  // trip keep the fragment-buffer index a compile-time constant; an odd step count just
-  // processes one more step of zeros.
+  // K step t lives in stage t%STAGES.  During step t a wave issues the MFMAs of step t, the LDS
+  // reads of step t+1, and the global loads of step t+STAGES-1 into the stage of step t-1.
+  //   * reads of step t+1 need that step landed for everybody: each wave waits for its own share
+  //     (vmcnt) and then meets the others at the barrier that opens step t;
+  //   * the refill overwrites the stage of step t-1: every wave consumed its fragments of step t-1
+  //     in the MFMAs it issued before arriving at the same barrier, so those reads have completed
+  //     and the barrier needs no wait on the LDS counter.
+  // Two steps per loop trip keep the fragment-buffer index a compile-time constant; an odd step
+  // count just processes one more step of zeros.
   static_assert(KK == 1, "one 32-wide k-block per K step");
   const int KT = (K + BK - 1) / BK;
 #pragma unroll
-  for (int t = 0; t < STAGES; ++t)
+  for (int t = 0; t < STAGES - 1; ++t)
 #pragma unroll
     for (int l = 0; l < S::LOADS; ++l) issue_load(t, t, l, kTail);   // steps past K arrive as zeros
-  wait_vmcnt<(STAGES - 1) * S::LOADS>();                         // step 0 has landed (this wave's part)
+  wait_vmcnt<(STAGES - 2) * S::LOADS>();                         // step 0 has landed (this wave's part)
   __syncthreads();                                               // ... and everybody else's
 #pragma unroll
   for (int bj = 0; bj < TN; ++bj) {
@@ -296,16 +304,18 @@ __global__ __launch_bounds__(S::NT) void gemm_bf16_kernel(const uint16_t* __rest
   for (int bi = 0; bi < TM; ++bi) read_a(0, bi);
 
   int stage = 0;                       // stage of step kt
+  int freed = STAGES - 1;              // stage of step kt-1, refilled during step kt
   auto step = [&](int kt, int cur, auto full) __attribute__((always_inline)) {
-    wait_vmcnt<(STAGES - 2) * S::LOADS>();   // step kt+1 has landed (this wave's part)
-    __syncthreads();
+    wait_vmcnt<(STAGES - 3) * S::LOADS>();   // step kt+1 has landed (this wave's part)
+    block_barrier();
     const int next = (stage + 1 == STAGES) ? 0 : stage + 1;
-    kblock(cur, next, kt + STAGES, stage, full);
+    kblock(cur, next, kt + STAGES - 1, freed, full);
+    freed = stage;
     stage = next;
   };
   const int full_steps = K / BK;       // steps 0 .. full_steps-1 lie wholly inside K
   int kt = 0;
-  for (; kt + 1 + STAGES < full_steps; kt += 2) {   // both refills of this trip fetch whole steps
+  for (; kt + STAGES < full_steps; kt += 2) {   // both refills of this trip fetch whole steps
     step(kt, 0, kFull);
     step(kt + 1, 1, kFull);
   }
