@@ -117,10 +117,10 @@ def main():
     ms, wall_ms = time_mode(swz, torch, a, b, c, swz.MODE_XCD_GROUPM, args.steps, args.warmup)
     tflops = flops / ms / 1e9
 
-    traffic = None
+    traffic, traffic_detail = None, None
     rec = TRAFFIC.get(args.workload, {}).get("xcd_groupm")
     if rec is not None and TRAFFIC["kernel_sha256"] == kernel_hash():
-        traffic = rec
+        traffic, traffic_detail = rec["total_bytes"], rec
 
     out = {
         "metric": "bf16 GEMM TFLOP/s + % MFMA peak + L2 hit rate, swizzled vs round-robin PID",
@@ -137,6 +137,7 @@ def main():
         "l2_hit_rate": "not measurable inside this process; rocprofv3 TCC_HIT/TCC_MISS summaries per workload and mode are under profiles/",
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": tflops / PEAK_BF16_TFLOPS, "traffic": traffic},
+        "traffic_detail": traffic_detail,
     }
 
     if not args.no_extras:

@@ -132,22 +132,20 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const unsigned char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
 }
 
-// 16 bytes per lane, global -> LDS at (wave-uniform) lds_base + lane*16.
+// 16 bytes per lane, global -> LDS at (wave-uniform) LDS byte address lds_base + lane*16.
 // Written as inline assembly on purpose: the compiler then keeps no book on these loads, so it
 // does not guard later LDS reads of the *other* stage with a conservative vmcnt(0); the kernel
 // waits for them itself (s_waitcnt vmcnt(0) before the barrier that publishes a stage).
-__device__ __forceinline__ void load_to_lds(const void* gptr, unsigned char* lds_base) {
-  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
-      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_base);   // wave-uniform by construction
+__device__ __forceinline__ void load_to_lds(const void* gptr, uint32_t lds_base) {
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(lds_base);   // wave-uniform by construction
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory", "m0");
 }
 
 // MODE is a template parameter so that each mapping shows up under its own kernel name in
 // profiler traces; only the decode below depends on it.
 // Same, with the source given as a wave-uniform base (SGPR pair) plus a 32-bit per-lane byte offset.
-__device__ __forceinline__ void load_to_lds_base_off(const void* base, uint32_t off, unsigned char* lds_base) {
-  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
-      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_base);
+__device__ __forceinline__ void load_to_lds_base_off(const void* base, uint32_t off, uint32_t lds_base) {
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(lds_base);
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(off), "s"(base) : "memory", "m0");
 }
 
@@ -201,17 +199,18 @@ __global__ __launch_bounds__(S::NT) void gemm_bf16_kernel(const uint16_t* __rest
   const size_t a_step = (size_t)BK * 2;           // bytes per K step along a row of A
   const size_t b_step = (size_t)BK * N * 2;       // bytes per K step down the rows of B
   const unsigned char* zero = reinterpret_cast<const unsigned char*>(&kZeroChunk);
+  const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;   // LDS byte address of the ring
 
   // Load number idx (0 .. LOADS-1) of K step kt into `stage`; A and B loads alternate.
   // full = the whole step lies inside K (uniform): no per-lane work at all.
   auto issue_load = [&](int kt, int stage, int idx, auto full) __attribute__((always_inline)) {
-    unsigned char* sA = smem + stage * S::STAGE_BYTES;
-    unsigned char* sB = sA + S::A_BYTES;
+    const uint32_t sA = smem_addr + stage * S::STAGE_BYTES;
+    const uint32_t sB = sA + S::A_BYTES;
     const int i = idx >> 1;
     const bool is_a = (idx & 1) == 0;
     const unsigned char* base = is_a ? a_tile + kt * a_step : b_tile + kt * b_step;
     const uint32_t off = is_a ? a_off[i] : b_off[i];
-    unsigned char* dst = is_a ? sA + (wave * S::A_LOADS + i) * 1024 : sB + (wave * S::B_LOADS + i) * 1024;
+    const uint32_t dst = is_a ? sA + (wave * S::A_LOADS + i) * 1024 : sB + (wave * S::B_LOADS + i) * 1024;
     if constexpr (decltype(full)::value) {
       load_to_lds_base_off(base, off, dst);
     } else {

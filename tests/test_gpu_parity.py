@@ -108,6 +108,39 @@ def test_ragged_shapes_full_matrix(swz, tile, M, N, K):
         assert np.array_equal(c, outs[0])
 
 
+@pytest.mark.parametrize("K", [8, 24, 32, 40, 64, 96, 104, 128, 136, 160, 168, 200, 232, 264, 1000])
+def test_every_k_tail_and_pipeline_depth(swz, K):
+    # K steps of 32: fewer steps than ring stages, odd and even step counts, partial last step,
+    # and the hand-over between the unpredicated and the predicated load path
+    M, N = 272, 264
+    a = si.matrix_bf16(300 + K, 0, M, K, "normal")
+    b = si.matrix_bf16(300 + K, 1, K, N, "uniform")
+    ref = gemm_ref.gemm(a, b)
+    for tile in (128, 256):
+        outs = run_modes(swz, a, b, modes=(0, 2), bm=tile, bn=tile)
+        assert_within_tolerance(outs[0], ref, f"K={K} tile {tile}")
+        assert np.array_equal(outs[0], outs[2])
+
+
+def test_garbage_beyond_the_edges_cannot_leak_into_c(swz):
+    # Rows >= M of A and columns >= N of B are fetched from clamped (valid) addresses, i.e. they are
+    # copies of real data: huge values in the last row / last columns must not disturb any stored element.
+    M, N, K = 300, 328, 96
+    a = si.matrix_bf16(41, 0, M, K, "uniform")
+    b = si.matrix_bf16(41, 1, K, N, "uniform")
+    a[-1, :] = si.f32_to_bf16_bits(np.full(K, 3.0e38, dtype=np.float32))     # finite, but products overflow
+    b[:, -8:] = si.f32_to_bf16_bits(np.full((K, 8), -3.0e38, dtype=np.float32))
+    ref = gemm_ref.gemm(a, b)
+    for tile in (128, 256):
+        c = run_modes(swz, a, b, modes=(2,), bm=tile, bn=tile)[2]
+        got = si.bf16_bits_to_f64(c)
+        clean = np.ones((M, N), dtype=bool)
+        clean[-1, :] = False
+        clean[:, -8:] = False
+        assert gemm_ref.within_tolerance(got[clean], ref[clean]).all()
+        assert np.isfinite(got[clean]).all()
+
+
 @pytest.mark.parametrize("tile", [128, 256])
 def test_small_integer_inputs_are_bit_exact(swz, tile):
     # entries in {-1,0,1}, K <= 256: every partial sum is an integer below 2^8, exact in fp32 and in bf16
