@@ -4,11 +4,17 @@ reader that turns rocprofv3's CSV output into the summaries kept with the measur
     python -m paper_2508_20258_amd.harness run --workload cfg2_4096 --mode xcd_groupm --launches 10
     python -m paper_2508_20258_amd.harness copy --mib 1024 --launches 3
     python -m paper_2508_20258_amd.harness summarize <rocprofv3 output dir>
+    python -m paper_2508_20258_amd.harness rank --workload cfg4_skinny
 
 `run` launches one mapping mode of one workload a fixed number of times, so that every GEMM
 dispatch in the trace belongs to that (workload, mode).  `copy` launches the plain copy kernel
 of known HBM traffic, against which FETCH_SIZE / WRITE_SIZE are scaled.  `summarize` prints,
 per kernel, the dispatch count, average duration, and the average of every counter found.
+`rank` is the non-LLM core of the paper's loop (Methodology, step 4): it profiles a list of
+candidate remaps (mapping mode x group_m), checks each one (a candidate whose C differs bitwise
+from the round-robin launch, or whose PID map is not a permutation, is a broken remap and is
+dropped), ranks the rest by L2 hit rate and names the best.  It starts one child process per
+measurement and never touches the GPU itself.
 The metric the paper ranks remaps by is the L2 hit rate (SwizzlePerf, Methodology step 2 and
 4): here  TCC_HIT / (TCC_HIT + TCC_MISS), from the summed TCC counters.
 """
@@ -34,6 +40,7 @@ def _inputs(workload):
 
 
 def cmd_run(args):
+    import numpy as np
     import torch
 
     import paper_2508_20258_amd as swz
@@ -44,10 +51,66 @@ def cmd_run(args):
         params.update(bm=args.tile, bn=args.tile)
     if args.group_m:
         params.update(group_m=args.group_m)
-    for _ in range(args.launches):
-        swz.gemm(a, b, c, mode=swz.MODES[args.mode], **params)
+    mode = swz.MODES[args.mode]
+    swz.gemm(a, b, c, mode=mode, **params)          # first launch: cold, outside the timing
     torch.cuda.synchronize()
-    print(f"ran {args.launches} launches of {args.workload} mode {args.mode}", flush=True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(max(args.launches - 1, 1)):
+        swz.gemm(a, b, c, mode=mode, **params)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / max(args.launches - 1, 1)
+    print(f"ran {args.launches} launches of {args.workload} mode {args.mode}: {us:.2f} us per launch", flush=True)
+    if args.check:
+        # remap purity: the bits must equal those of the round-robin launch; the map must be a permutation
+        ref = torch.empty_like(c)
+        swz.gemm(a, b, ref, mode=swz.MODE_RR, **params)
+        torch.cuda.synchronize()
+        plan = swz.gemm_plan(a.shape[0], b.shape[1], a.shape[1], **params)
+        m = swz.pid_map(plan["grid_m"], plan["grid_n"], plan["num_xcd"], plan["group_m"], mode)
+        perm_ok = bool((np.sort(m) == np.arange(m.size)).all())
+        same = bool(torch.equal(c.view(torch.int16), ref.view(torch.int16)))
+        print(f"check: bit_identical_to_rr={same} map_is_permutation={perm_ok} us_per_launch={us:.3f}", flush=True)
+
+
+def cmd_rank(args):
+    """Profile candidate remaps in child processes and rank them by measured L2 hit rate."""
+    import json
+    import shutil
+    import subprocess
+    import tempfile
+    env = dict(os.environ, TMPDIR=os.environ.get("TMPDIR", "/tmp"))
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    me = [sys.executable, "-m", "paper_2508_20258_amd.harness", "run", "--workload", args.workload, "--launches", str(args.launches)]
+    cands = [("rr", 0), ("xcd", 0)] + [(m, g) for m in ("xcd_groupm", "groupm") for g in args.group_m]
+    rows = []
+    for mode, g in cands:
+        extra = ["--mode", mode] + (["--group-m", str(g)] if g else [])
+        chk = subprocess.run(me + extra + ["--check"], cwd=root, env=env, capture_output=True, text=True, timeout=600)
+        line = next((l for l in chk.stdout.splitlines() if l.startswith("check:")), "")
+        valid = "bit_identical_to_rr=True" in line and "map_is_permutation=True" in line
+        us = float(line.split("us_per_launch=")[1]) if "us_per_launch=" in line else float("nan")
+        out = tempfile.mkdtemp(prefix="swz_rank_")
+        try:
+            prof = subprocess.run(["rocprofv3", "--pmc", "TCC_HIT", "TCC_MISS", "--output-format", "json", "-d", out, "--"] + me + extra,
+                                  cwd=root, env=env, capture_output=True, text=True, timeout=600)
+            hit = float("nan")
+            if prof.returncode == 0:
+                for d in summarize_json(out, "gemm").values():
+                    h, m = d["counters"]["TCC_HIT"]["total"], d["counters"]["TCC_MISS"]["total"]
+                    hit = 100.0 * h / (h + m)
+        finally:
+            shutil.rmtree(out, ignore_errors=True)
+        rows.append(dict(mode=mode, group_m=g or None, valid=valid, l2_hit_pct=hit, us_per_launch=us))
+        print(f"candidate {mode:11s} group_m={g or '-':>2}: valid={valid} L2 hit {hit:6.2f} %  {us:9.2f} us", flush=True)
+    good = sorted((r for r in rows if r["valid"] and r["l2_hit_pct"] == r["l2_hit_pct"]), key=lambda r: -r["l2_hit_pct"])
+    print("ranking by L2 hit rate (ties: faster first):")
+    for r in sorted(good, key=lambda r: (-round(r["l2_hit_pct"], 1), r["us_per_launch"])):
+        print(f"  {r['mode']:11s} group_m={r['group_m'] or '-':>2}  {r['l2_hit_pct']:6.2f} %  {r['us_per_launch']:9.2f} us")
+    if good:
+        best = sorted(good, key=lambda r: (-round(r["l2_hit_pct"], 1), r["us_per_launch"]))[0]
+        print("best validated candidate: " + json.dumps(best))
 
 
 def cmd_copy(args):
@@ -167,7 +230,13 @@ def main(argv=None):
     r.add_argument("--launches", type=int, default=10)
     r.add_argument("--tile", type=int, default=0)
     r.add_argument("--group-m", type=int, default=0)
+    r.add_argument("--check", action="store_true", help="also compare the bits with a round-robin launch")
     r.set_defaults(fn=cmd_run)
+    k = sub.add_parser("rank")
+    k.add_argument("--workload", default="cfg4_skinny")
+    k.add_argument("--launches", type=int, default=4)
+    k.add_argument("--group-m", type=int, nargs="+", default=[1, 2, 4, 8, 16])
+    k.set_defaults(fn=cmd_rank)
     c = sub.add_parser("copy")
     c.add_argument("--mib", type=int, default=1024)
     c.add_argument("--launches", type=int, default=3)
