@@ -49,6 +49,8 @@ typedef struct {
   int32_t bk;      /* K panel per tile step: 64 (the kernel streams it as two 32-wide halves) */
   int32_t group_m; /* tile rows per band of the grouped raster (default 4) */
   int32_t num_xcd; /* XCD count assumed by the renumbering (default: detected; 8 on an unpartitioned MI355X) */
+  int32_t persistent; /* 0: one workgroup per tile (default); 1: persistent grid, see swz_pid_map_persistent */
+  int32_t num_wg;  /* persistent grid size (default: one workgroup per compute unit, at most one per tile) */
 } swz_params;
 
 const char* swz_status_string(int status);
@@ -78,6 +80,23 @@ int swz_pid_map(int grid_m, int grid_n, int num_xcd, int group_m, int mode, int3
 int swz_pid_map_device(int grid_m, int grid_n, int num_xcd, int group_m, int mode, int32_t* d_tile,
                        int32_t* d_xcc, hipStream_t stream);
 
+/* The PID map of the persistent launch style (the one the paper's GEMM listing uses: the number
+ * of workgroups equals the number of compute units and each workgroup loops over tiles).
+ * num_wg workgroups; workgroup w is renumbered among the WORKGROUPS (p = XCD renumbering of w
+ * over num_wg ids in modes 1/2, p = w otherwise) and computes in round i the tile the raster
+ * visits (p + i*num_wg)-th.
+ *   out : caller-owned HOST buffer of rounds*num_wg int32, rounds = ceil(grid_m*grid_n / num_wg);
+ *         out[i*num_wg + w] = pm*grid_n + pn, or -1 where workgroup w has no tile in round i.
+ * Every tile appears exactly once.  Errors as swz_pid_map; num_wg < 1 is INVALID_ARG. */
+int swz_pid_map_persistent(int grid_m, int grid_n, int num_xcd, int group_m, int mode, int num_wg, int32_t* out);
+
+/* Same map from the DEVICE code of the persistent GEMM kernel (num_wg workgroups are launched).
+ *   d_tile : DEVICE buffer of rounds*num_wg int32, laid out as above;
+ *   d_xcc  : optional DEVICE buffer of num_wg int32, the XCD each workgroup ran on.
+ * Asynchronous on `stream`; never allocates or synchronises. */
+int swz_pid_map_persistent_device(int grid_m, int grid_n, int num_xcd, int group_m, int mode, int num_wg,
+                                  int32_t* d_tile, int32_t* d_xcc, hipStream_t stream);
+
 /* C = A . B  (paper's GEMM case study: A is M x K, B is K x N, C is M x N), one workgroup per
  * output tile, workgroup ids remapped according to `mode`.
  *   A, B, C : caller-owned DEVICE pointers, row-major, densely packed (lda = K, ldb = N,
@@ -94,8 +113,9 @@ int swz_pid_map_device(int grid_m, int grid_n, int num_xcd, int group_m, int mod
 int swz_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,
              hipStream_t stream);
 
-/* swz_gemm with explicit tile shape / group_m / num_xcd (null params = all defaults).
- * UNSUPPORTED for a tile shape other than 128x128x64 or 256x256x64. */
+/* swz_gemm with explicit tile shape / group_m / num_xcd / launch style (null params = all defaults).
+ * UNSUPPORTED for a tile shape other than 128x128x64 or 256x256x64.  The persistent launch computes
+ * every tile with the same instruction sequence, so its C is bit-identical to the default launch. */
 int swz_gemm_ex(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,
                 const swz_params* params, hipStream_t stream);
 

@@ -72,6 +72,34 @@ def pid_map(grid_m: int, grid_n: int, num_xcd: int, group_m: int, mode: int) -> 
     return out
 
 
+def pid_map_persistent(grid_m: int, grid_n: int, num_xcd: int, group_m: int, mode: int, num_wg: int) -> list[list[int]]:
+    """Persistent launch (the paper's own GEMM listing: as many workgroups as compute units, each
+    looping over tiles).  rounds[i][w] = tile workgroup w computes in round i, or -1.
+
+    The workgroups (not the tiles) are dealt to the XCDs and renumbered XCD by XCD; workgroup w with
+    new number p then takes the raster positions p, p + num_wg, p + 2*num_wg, ...
+    """
+    if grid_m < 1 or grid_n < 1 or num_xcd < 1 or group_m < 1 or num_wg < 1 or mode not in (0, 1, 2, 3):
+        raise ValueError("bad arguments")
+    total = grid_m * grid_n
+    p_of_w = logical_ids(num_wg, num_xcd, xcd_remap=mode in (MODE_XCD, MODE_XCD_GROUPM))
+    order = raster_order(grid_m, grid_n, group_m, grouped=mode in (MODE_XCD_GROUPM, MODE_GROUPM))
+    rounds = []
+    start = 0
+    while start < total:
+        row = []
+        for w in range(num_wg):
+            pos = start + p_of_w[w]
+            if pos < total:
+                pm, pn = order[pos]
+                row.append(pm * grid_n + pn)
+            else:
+                row.append(-1)
+        rounds.append(row)
+        start += num_wg
+    return rounds
+
+
 # ----------------------------------------------------------------------------------------
 # Invariant checkers: they judge ANY candidate map (the oracle's, the library's, a broken one).
 # ----------------------------------------------------------------------------------------

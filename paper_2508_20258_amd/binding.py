@@ -17,12 +17,13 @@ MODES = {"rr": MODE_RR, "xcd": MODE_XCD, "xcd_groupm": MODE_XCD_GROUPM, "groupm"
 DTYPE_BF16 = 0
 
 EXPORTS = ("swz_status_string", "swz_device_info", "swz_pid_map", "swz_pid_map_device", "swz_gemm", "swz_gemm_ex",
-           "swz_gemm_plan", "swz_copy_bytes")
+           "swz_gemm_plan", "swz_copy_bytes", "swz_pid_map_persistent", "swz_pid_map_persistent_device")
 
 
 class SwzParams(ctypes.Structure):
     _fields_ = [("bm", ctypes.c_int32), ("bn", ctypes.c_int32), ("bk", ctypes.c_int32),
-                ("group_m", ctypes.c_int32), ("num_xcd", ctypes.c_int32)]
+                ("group_m", ctypes.c_int32), ("num_xcd", ctypes.c_int32), ("persistent", ctypes.c_int32),
+                ("num_wg", ctypes.c_int32)]
 
 
 class SwzError(RuntimeError):
@@ -66,6 +67,8 @@ def _load() -> ctypes.CDLL:
     L.swz_gemm_ex.argtypes = [vp, vp, vp, i64, i64, i64, i, i, pp, vp]
     L.swz_gemm_plan.argtypes = [i64, i64, i64, pp, pp, ip, ip]
     L.swz_copy_bytes.argtypes = [vp, vp, i64, vp]
+    L.swz_pid_map_persistent.argtypes = [i, i, i, i, i, i, vp]
+    L.swz_pid_map_persistent_device.argtypes = [i, i, i, i, i, i, vp, vp, vp]
     for name in EXPORTS:
         if name != "swz_status_string":
             getattr(L, name).restype = i
@@ -90,8 +93,8 @@ def _stream_handle(stream) -> int:
     return int(s.cuda_stream)
 
 
-def _params(bm=0, bn=0, bk=0, group_m=0, num_xcd=0) -> SwzParams:
-    return SwzParams(int(bm), int(bn), int(bk), int(group_m), int(num_xcd))
+def _params(bm=0, bn=0, bk=0, group_m=0, num_xcd=0, persistent=0, num_wg=0) -> SwzParams:
+    return SwzParams(int(bm), int(bn), int(bk), int(group_m), int(num_xcd), int(persistent), int(num_wg))
 
 
 def device_info() -> dict:
@@ -128,14 +131,15 @@ def gemm_plan(M: int, N: int, K: int, **params) -> dict:
     p = _params(**params)
     _check(lib.swz_gemm_plan(int(M), int(N), int(K), ctypes.byref(p), ctypes.byref(r), ctypes.byref(gm),
                              ctypes.byref(gn)), "swz_gemm_plan")
-    return dict(bm=r.bm, bn=r.bn, bk=r.bk, group_m=r.group_m, num_xcd=r.num_xcd, grid_m=gm.value, grid_n=gn.value)
+    return dict(bm=r.bm, bn=r.bn, bk=r.bk, group_m=r.group_m, num_xcd=r.num_xcd, persistent=r.persistent,
+                num_wg=r.num_wg, grid_m=gm.value, grid_n=gn.value)
 
 
 def gemm(a, b, c=None, mode: int = MODE_XCD_GROUPM, stream=None, **params):
     """C = A @ B on the GPU through swz_gemm / swz_gemm_ex.
 
     a (M x K), b (K x N): contiguous torch.bfloat16 CUDA tensors; c (M x N) is allocated if not given.
-    Keyword params (bm, bn, bk, group_m, num_xcd) select swz_gemm_ex.
+    Keyword params (bm, bn, bk, group_m, num_xcd, persistent, num_wg) select swz_gemm_ex.
     """
     import torch
     assert a.is_cuda and b.is_cuda and a.dtype == torch.bfloat16 and b.dtype == torch.bfloat16
@@ -160,3 +164,29 @@ def copy_bytes(src, dst, stream=None) -> None:
     nbytes = src.numel() * src.element_size()
     assert src.is_cuda and dst.is_cuda and dst.numel() * dst.element_size() == nbytes
     _check(lib.swz_copy_bytes(src.data_ptr(), dst.data_ptr(), nbytes, _stream_handle(stream)), "swz_copy_bytes")
+
+
+def _rounds(grid_m: int, grid_n: int, num_wg: int) -> int:
+    n = int(grid_m) * int(grid_n)
+    return -(-n // int(num_wg)) if 0 < n < (1 << 31) and num_wg > 0 else 1
+
+
+def pid_map_persistent(grid_m: int, grid_n: int, num_xcd: int, group_m: int, mode: int, num_wg: int) -> np.ndarray:
+    """Host PID map of the persistent launch: out[round, w] = tile or -1 (int32, shape rounds x num_wg)."""
+    rounds = _rounds(grid_m, grid_n, num_wg)
+    out = np.full((rounds, max(int(num_wg), 1)), -2, dtype=np.int32)
+    _check(lib.swz_pid_map_persistent(int(grid_m), int(grid_n), int(num_xcd), int(group_m), int(mode), int(num_wg),
+                                      out.ctypes.data), "swz_pid_map_persistent")
+    return out
+
+
+def pid_map_persistent_device(grid_m: int, grid_n: int, num_xcd: int, group_m: int, mode: int, num_wg: int, stream=None):
+    """Device PID map of the persistent launch: (tile [rounds x num_wg], xcc [num_wg]) int32 CUDA tensors."""
+    import torch
+    rounds = _rounds(grid_m, grid_n, num_wg)
+    tile = torch.full((rounds, max(int(num_wg), 1)), -2, dtype=torch.int32, device="cuda")
+    xcc = torch.full((max(int(num_wg), 1),), -1, dtype=torch.int32, device="cuda")
+    _check(lib.swz_pid_map_persistent_device(int(grid_m), int(grid_n), int(num_xcd), int(group_m), int(mode), int(num_wg),
+                                             tile.data_ptr(), xcc.data_ptr(), _stream_handle(stream)),
+           "swz_pid_map_persistent_device")
+    return tile, xcc

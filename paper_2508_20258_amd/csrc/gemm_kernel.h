@@ -141,24 +141,20 @@ __device__ __forceinline__ void load_to_lds(const void* gptr, uint32_t lds_base)
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory", "m0");
 }
 
-// MODE is a template parameter so that each mapping shows up under its own kernel name in
-// profiler traces; only the decode below depends on it.
 // Same, with the source given as a wave-uniform base (SGPR pair) plus a 32-bit per-lane byte offset.
 __device__ __forceinline__ void load_to_lds_base_off(const void* base, uint32_t off, uint32_t lds_base) {
   const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(lds_base);
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(off), "s"(base) : "memory", "m0");
 }
 
-template <class S, int MODE>
-__global__ __launch_bounds__(S::NT) void gemm_bf16_kernel(const uint16_t* __restrict__ A,
-                                                          const uint16_t* __restrict__ B,
-                                                          uint16_t* __restrict__ C, int M, int N, int K,
-                                                          int grid_m, int grid_n, int num_xcd, int group_m) {
+// One BM x BN tile of C, tile row pm, tile column pn, by the whole workgroup.  On return every
+// wave has issued its stores; LDS may still be read by slower waves (callers that reuse it put a
+// barrier first).
+template <class S>
+__device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
+                                          uint16_t* __restrict__ C, int M, int N, int K, int pm, int pn,
+                                          unsigned char* smem) {
   constexpr int BM = S::BM, BN = S::BN, BK = S::BK, KK = S::KK, TM = S::TM, TN = S::TN, STAGES = S::STAGES;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-
-  int pm, pn;
-  swz_decode_tile((int)blockIdx.x, grid_m, grid_n, num_xcd, group_m, MODE, &pm, &pn);
   const int m0 = pm * BM;
   const int n0 = pn * BN;
 
@@ -353,6 +349,40 @@ __global__ __launch_bounds__(S::NT) void gemm_bf16_kernel(const uint16_t* __rest
   }
 }
 
+// One workgroup per tile.  MODE is a template parameter so that each mapping shows up under its
+// own kernel name in profiler traces; only the decode depends on it.
+template <class S, int MODE>
+__global__ __launch_bounds__(S::NT) void gemm_bf16_kernel(const uint16_t* __restrict__ A,
+                                                          const uint16_t* __restrict__ B,
+                                                          uint16_t* __restrict__ C, int M, int N, int K,
+                                                          int grid_m, int grid_n, int num_xcd, int group_m) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  int pm, pn;
+  swz_decode_tile((int)blockIdx.x, grid_m, grid_n, num_xcd, group_m, MODE, &pm, &pn);
+  gemm_tile<S>(A, B, C, M, N, K, pm, pn, smem);
+}
+
+// Persistent grid: gridDim.x workgroups (one per compute unit) stay resident; workgroup w is
+// renumbered among the workgroups and walks the raster with stride gridDim.x, the launch style
+// of the paper's GEMM case study (Appendix "Case Study: GEMM Swizzling", num_blocks = number of
+// compute units).
+template <class S, int MODE>
+__global__ __launch_bounds__(S::NT) void gemm_bf16_persistent_kernel(const uint16_t* __restrict__ A,
+                                                                     const uint16_t* __restrict__ B,
+                                                                     uint16_t* __restrict__ C, int M, int N, int K,
+                                                                     int grid_m, int grid_n, int num_xcd, int group_m) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int total = grid_m * grid_n;
+  for (int round = 0;; ++round) {
+    const int l = swz_persistent_logical((int)blockIdx.x, round, (int)gridDim.x, total, num_xcd, MODE);
+    if (l < 0) break;                      // uniform: the whole workgroup leaves together
+    int pm, pn;
+    swz_raster(l, grid_m, grid_n, group_m, swz_mode_grouped(MODE), &pm, &pn);
+    gemm_tile<S>(A, B, C, M, N, K, pm, pn, smem);
+    __syncthreads();                       // the next tile's loads overwrite LDS the epilogue read
+  }
+}
+
 // Runs only the device PID decode: one workgroup per tile, recording the tile it would
 // compute and the XCD it actually landed on (hardware register XCC_ID, bits 3:0).
 __global__ void pid_map_kernel(int grid_m, int grid_n, int num_xcd, int group_m, int mode,
@@ -362,6 +392,25 @@ __global__ void pid_map_kernel(int grid_m, int grid_n, int num_xcd, int group_m,
   int pm, pn;
   swz_decode_tile(w, grid_m, grid_n, num_xcd, group_m, mode, &pm, &pn);
   tile[w] = pm * grid_n + pn;
+  if (xcc != nullptr) xcc[w] = (int32_t)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11));
+}
+
+// Persistent flavour: gridDim.x workgroups; workgroup w records, for every round i, the tile it
+// would compute (or -1) at tile[i*gridDim.x + w], and once the XCD it ran on at xcc[w].
+__global__ void pid_map_persistent_kernel(int grid_m, int grid_n, int num_xcd, int group_m, int mode, int rounds,
+                                          int32_t* __restrict__ tile, int32_t* __restrict__ xcc) {
+  if (threadIdx.x != 0) return;
+  const int w = (int)blockIdx.x, g = (int)gridDim.x;
+  for (int round = 0; round < rounds; ++round) {
+    const int l = swz_persistent_logical(w, round, g, grid_m * grid_n, num_xcd, mode);
+    int t = -1;
+    if (l >= 0) {
+      int pm, pn;
+      swz_raster(l, grid_m, grid_n, group_m, swz_mode_grouped(mode), &pm, &pn);
+      t = pm * grid_n + pn;
+    }
+    tile[(size_t)round * g + w] = t;
+  }
   if (xcc != nullptr) xcc[w] = (int32_t)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11));
 }
 

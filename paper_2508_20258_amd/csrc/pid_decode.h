@@ -28,19 +28,19 @@
 
 enum : int { kModeRR = 0, kModeXcd = 1, kModeXcdGroupM = 2, kModeGroupM = 3 };
 
-// Requires: 1 <= grid_m, grid_n, num_xcd; 1 <= group_m <= grid_m; grid_m*grid_n < 2^31;
-// 0 <= w < grid_m*grid_n.  All intermediate values are <= grid_m*grid_n.
-SWZ_HD void swz_decode_tile(int w, int grid_m, int grid_n, int num_xcd, int group_m, int mode, int* pm, int* pn) {
-  const int total = grid_m * grid_n;
-  int l = w;
-  if (mode == kModeXcd || mode == kModeXcdGroupM) {
-    const int q = total / num_xcd;
-    const int r = total - q * num_xcd;
-    const int i = w / num_xcd;
-    const int x = w - i * num_xcd;
-    l = x * q + (x < r ? x : r) + i;
-  }
-  if (mode == kModeXcdGroupM || mode == kModeGroupM) {
+// XCD renumbering of id w among `total` ids dealt round-robin to num_xcd XCDs (see the proof above).
+// Requires 1 <= num_xcd, 0 <= w < total < 2^31.
+SWZ_HD int swz_xcd_renumber(int w, int total, int num_xcd) {
+  const int q = total / num_xcd;
+  const int r = total - q * num_xcd;
+  const int i = w / num_xcd;
+  const int x = w - i * num_xcd;
+  return x * q + (x < r ? x : r) + i;
+}
+
+// Tile (pm, pn) visited l-th by the raster.  Requires 1 <= group_m <= grid_m, 0 <= l < grid_m*grid_n.
+SWZ_HD void swz_raster(int l, int grid_m, int grid_n, int group_m, bool grouped, int* pm, int* pn) {
+  if (grouped) {
     const int width = group_m * grid_n;
     const int band = l / width;
     const int k = l - band * width;
@@ -54,4 +54,26 @@ SWZ_HD void swz_decode_tile(int w, int grid_m, int grid_n, int num_xcd, int grou
     *pm = row;
     *pn = l - row * grid_n;
   }
+}
+
+SWZ_HD bool swz_mode_renumbers(int mode) { return mode == kModeXcd || mode == kModeXcdGroupM; }
+SWZ_HD bool swz_mode_grouped(int mode) { return mode == kModeXcdGroupM || mode == kModeGroupM; }
+
+// One workgroup per tile.  Requires: 1 <= grid_m, grid_n, num_xcd; 1 <= group_m <= grid_m;
+// grid_m*grid_n < 2^31; 0 <= w < grid_m*grid_n.  All intermediate values are <= grid_m*grid_n.
+SWZ_HD void swz_decode_tile(int w, int grid_m, int grid_n, int num_xcd, int group_m, int mode, int* pm, int* pn) {
+  const int total = grid_m * grid_n;
+  const int l = swz_mode_renumbers(mode) ? swz_xcd_renumber(w, total, num_xcd) : w;
+  swz_raster(l, grid_m, grid_n, group_m, swz_mode_grouped(mode), pm, pn);
+}
+
+// Persistent grid (the launch style of the paper's own GEMM listing: num_blocks = number of
+// compute units): num_wg workgroups stay resident and workgroup w computes, in round
+// i = 0, 1, ..., the logical tile  p + i*num_wg,  where p is w renumbered among the num_wg
+// workgroups (not among the tiles).  p ranges over [0, num_wg) bijectively, so p + i*num_wg
+// visits every logical id in [0, T) exactly once.  Returns the logical id, or -1 once past T.
+SWZ_HD int swz_persistent_logical(int w, int round, int num_wg, int total, int num_xcd, int mode) {
+  const int p = swz_mode_renumbers(mode) ? swz_xcd_renumber(w, num_wg, num_xcd) : w;
+  const int64_t l = (int64_t)p + (int64_t)round * num_wg;
+  return l < total ? (int)l : -1;
 }

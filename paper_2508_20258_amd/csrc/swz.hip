@@ -20,7 +20,7 @@ struct DeviceFacts {
   int num_xcd = 0, cus = 0, l2_bytes = 0, lds_bytes = 0;
 };
 DeviceFacts g_facts[kMaxDevices];
-bool g_attr_set[kMaxDevices][2][4];
+bool g_attr_set[kMaxDevices][2][4][2];
 std::mutex g_mu;
 
 int query_device(DeviceFacts* out) {
@@ -54,22 +54,25 @@ int check_map_args(int grid_m, int grid_n, int num_xcd, int* group_m, int mode) 
   return SWZ_OK;
 }
 
+// num_wg == 0: one workgroup per tile; otherwise the persistent kernel with num_wg workgroups.
 template <class S, int MODE>
 int launch_gemm_mode(const void* A, const void* B, void* C, int M, int N, int K, int grid_m, int grid_n,
-                     int num_xcd, int group_m, hipStream_t stream, int slot) {
-  auto kernel = swz::gemm_bf16_kernel<S, MODE>;
+                     int num_xcd, int group_m, int num_wg, hipStream_t stream, int slot) {
+  auto kernel = num_wg > 0 ? swz::gemm_bf16_persistent_kernel<S, MODE> : swz::gemm_bf16_kernel<S, MODE>;
+  const int style = num_wg > 0 ? 1 : 0;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SWZ_ERR_HIP;
   {
     std::lock_guard<std::mutex> lock(g_mu);
-    if (!g_attr_set[dev][slot][MODE]) {
+    if (!g_attr_set[dev][slot][MODE][style]) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                               S::LDS_BYTES) != hipSuccess)
         return SWZ_ERR_HIP;
-      g_attr_set[dev][slot][MODE] = true;
+      g_attr_set[dev][slot][MODE][style] = true;
     }
   }
-  hipLaunchKernelGGL(kernel, dim3((unsigned)(grid_m * grid_n)), dim3(S::NT), S::LDS_BYTES, stream,
+  const unsigned blocks = (unsigned)(num_wg > 0 ? num_wg : grid_m * grid_n);
+  hipLaunchKernelGGL(kernel, dim3(blocks), dim3(S::NT), S::LDS_BYTES, stream,
                      static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(B), static_cast<uint16_t*>(C),
                      M, N, K, grid_m, grid_n, num_xcd, group_m);
   return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
@@ -77,12 +80,12 @@ int launch_gemm_mode(const void* A, const void* B, void* C, int M, int N, int K,
 
 template <class S>
 int launch_gemm(const void* A, const void* B, void* C, int M, int N, int K, int grid_m, int grid_n,
-                int num_xcd, int group_m, int mode, hipStream_t stream, int slot) {
+                int num_xcd, int group_m, int mode, int num_wg, hipStream_t stream, int slot) {
   switch (mode) {
-    case SWZ_MODE_RR: return launch_gemm_mode<S, kModeRR>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, stream, slot);
-    case SWZ_MODE_XCD: return launch_gemm_mode<S, kModeXcd>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, stream, slot);
-    case SWZ_MODE_XCD_GROUPM: return launch_gemm_mode<S, kModeXcdGroupM>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, stream, slot);
-    case SWZ_MODE_GROUPM: return launch_gemm_mode<S, kModeGroupM>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, stream, slot);
+    case SWZ_MODE_RR: return launch_gemm_mode<S, kModeRR>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, num_wg, stream, slot);
+    case SWZ_MODE_XCD: return launch_gemm_mode<S, kModeXcd>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, num_wg, stream, slot);
+    case SWZ_MODE_XCD_GROUPM: return launch_gemm_mode<S, kModeXcdGroupM>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, num_wg, stream, slot);
+    case SWZ_MODE_GROUPM: return launch_gemm_mode<S, kModeGroupM>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, num_wg, stream, slot);
     default: return SWZ_ERR_INVALID_ARG;
   }
 }
@@ -91,23 +94,28 @@ int resolve_plan(int64_t M, int64_t N, int64_t K, const swz_params* p, swz_param
   if (M < 1 || N < 1 || K < 1) return SWZ_ERR_INVALID_ARG;
   const int64_t lim = (int64_t)1 << 31;
   if (M >= lim || N >= lim || K >= lim) return SWZ_ERR_OVERFLOW;
-  swz_params q = {0, 0, 0, 0, 0};
+  swz_params q = {0, 0, 0, 0, 0, 0, 0};
   if (p != nullptr) q = *p;
-  if (q.bm < 0 || q.bn < 0 || q.bk < 0 || q.group_m < 0 || q.num_xcd < 0) return SWZ_ERR_INVALID_ARG;
+  if (q.bm < 0 || q.bn < 0 || q.bk < 0 || q.group_m < 0 || q.num_xcd < 0 || q.num_wg < 0 ||
+      (q.persistent != 0 && q.persistent != 1))
+    return SWZ_ERR_INVALID_ARG;
   if (q.bm == 0 && q.bn == 0) q.bm = q.bn = (M <= 512 && N <= 512) ? 128 : 256;
   if (q.bm == 0) q.bm = q.bn;
   if (q.bn == 0) q.bn = q.bm;
   if (q.bk == 0) q.bk = kDefaultBK;
   if (q.group_m == 0) q.group_m = 4;
   if (!((q.bm == 128 && q.bn == 128) || (q.bm == 256 && q.bn == 256)) || q.bk != kDefaultBK) return SWZ_ERR_UNSUPPORTED;
-  if (q.num_xcd == 0) {
+  const int64_t gm = (M + q.bm - 1) / q.bm, gn = (N + q.bn - 1) / q.bn;
+  if (gm * gn >= lim) return SWZ_ERR_OVERFLOW;
+  if (q.num_xcd == 0 || (q.persistent && q.num_wg == 0)) {
     DeviceFacts f;
     const int st = query_device(&f);
     if (st != SWZ_OK) return st;
-    q.num_xcd = f.num_xcd;
+    if (q.num_xcd == 0) q.num_xcd = f.num_xcd;
+    if (q.persistent && q.num_wg == 0) q.num_wg = f.cus;
   }
-  const int64_t gm = (M + q.bm - 1) / q.bm, gn = (N + q.bn - 1) / q.bn;
-  if (gm * gn >= lim) return SWZ_ERR_OVERFLOW;
+  if (!q.persistent) q.num_wg = 0;
+  else if (q.num_wg > gm * gn) q.num_wg = (int32_t)(gm * gn);   // never more workgroups than tiles
   if (r != nullptr) *r = q;
   if (grid_m != nullptr) *grid_m = (int)gm;
   if (grid_n != nullptr) *grid_n = (int)gn;
@@ -163,6 +171,40 @@ int swz_pid_map_device(int grid_m, int grid_n, int num_xcd, int group_m, int mod
   return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
 }
 
+int swz_pid_map_persistent(int grid_m, int grid_n, int num_xcd, int group_m, int mode, int num_wg, int32_t* out) {
+  if (out == nullptr || num_wg < 1) return SWZ_ERR_INVALID_ARG;
+  const int st = check_map_args(grid_m, grid_n, num_xcd, &group_m, mode);
+  if (st != SWZ_OK) return st;
+  const int total = grid_m * grid_n;
+  const int64_t rounds = ((int64_t)total + num_wg - 1) / num_wg;
+  if (rounds * num_wg >= (int64_t)1 << 31) return SWZ_ERR_OVERFLOW;
+  for (int round = 0; round < (int)rounds; ++round) {
+    for (int w = 0; w < num_wg; ++w) {
+      const int l = swz_persistent_logical(w, round, num_wg, total, num_xcd, mode);
+      int t = -1;
+      if (l >= 0) {
+        int pm, pn;
+        swz_raster(l, grid_m, grid_n, group_m, swz_mode_grouped(mode), &pm, &pn);
+        t = pm * grid_n + pn;
+      }
+      out[(size_t)round * num_wg + w] = t;
+    }
+  }
+  return SWZ_OK;
+}
+
+int swz_pid_map_persistent_device(int grid_m, int grid_n, int num_xcd, int group_m, int mode, int num_wg,
+                                  int32_t* d_tile, int32_t* d_xcc, hipStream_t stream) {
+  if (d_tile == nullptr || num_wg < 1) return SWZ_ERR_INVALID_ARG;
+  const int st = check_map_args(grid_m, grid_n, num_xcd, &group_m, mode);
+  if (st != SWZ_OK) return st;
+  const int64_t rounds = ((int64_t)grid_m * grid_n + num_wg - 1) / num_wg;
+  if (rounds * num_wg >= (int64_t)1 << 31) return SWZ_ERR_OVERFLOW;
+  hipLaunchKernelGGL(swz::pid_map_persistent_kernel, dim3((unsigned)num_wg), dim3(64), 0, stream, grid_m, grid_n,
+                     num_xcd, group_m, mode, (int)rounds, d_tile, d_xcc);
+  return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
+}
+
 int swz_copy_bytes(const void* src, void* dst, int64_t bytes, hipStream_t stream) {
   if (src == nullptr || dst == nullptr || bytes < 16) return SWZ_ERR_INVALID_ARG;
   if ((bytes & 15) || ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15)) return SWZ_ERR_UNSUPPORTED;
@@ -197,9 +239,9 @@ int swz_gemm_ex(const void* A, const void* B, void* C, int64_t M, int64_t N, int
   if (st != SWZ_OK) return st;
   if (r.bm == 128)
     return launch_gemm<swz::GemmShape<128, 128, 32, 4, 2, 2>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
-                                                       group_m, mode, stream, 0);
+                                                               group_m, mode, r.num_wg, stream, 0);
   return launch_gemm<swz::GemmShape<256, 256, 32, 4, 2, 4>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
-                                                     group_m, mode, stream, 1);
+                                                             group_m, mode, r.num_wg, stream, 1);
 }
 
 int swz_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,

@@ -256,3 +256,35 @@ def test_config5_with_128_tiles_has_a_ragged_xcd_share(swz):
     ii, jj = sample_indices(M, N, 128, 128, seed=5)
     assert_within_tolerance(outs[0][ii, jj], gemm_ref.gemm_elems(a, b, ii, jj), "cfg5/128 samples")
     assert not np.isnan(si.bf16_bits_to_f64(outs[0])).any()
+
+
+# ---------------------------------------------------------------------------- persistent launch style
+
+@pytest.mark.parametrize("gm,gn,X,g,G", [(16, 16, 8, 4, 256), (40, 28, 8, 4, 256), (5, 7, 8, 4, 6), (7, 3, 4, 2, 10), (3, 3, 8, 4, 9)])
+def test_persistent_device_decode_is_bit_exact_with_oracle(swz, gm, gn, X, g, G):
+    for mode in range(4):
+        tile, _ = swz.pid_map_persistent_device(gm, gn, X, g, mode, G)
+        torch.cuda.synchronize()
+        assert tile.cpu().numpy().tolist() == opm.pid_map_persistent(gm, gn, X, g, mode, G), (mode,)
+
+
+@pytest.mark.parametrize("M,N,K,G", [(1300, 1096, 200, 7), (1300, 1096, 200, 256), (640, 776, 96, 3), (300, 264, 64, 1)])
+def test_persistent_gemm_matches_oracle_and_the_default_launch_bitwise(swz, M, N, K, G):
+    a = si.matrix_bf16(500 + G, 0, M, K, "normal")
+    b = si.matrix_bf16(500 + G, 1, K, N, "uniform")
+    ref = gemm_ref.gemm(a, b)
+    for tile in (128, 256):
+        base = run_modes(swz, a, b, modes=(0,), bm=tile, bn=tile)[0]
+        assert_within_tolerance(base, ref, "default launch")
+        outs = run_modes(swz, a, b, bm=tile, bn=tile, persistent=1, num_wg=G)
+        for mode, c in outs.items():
+            assert np.array_equal(c, base), f"persistent mode {mode} tile {tile} G {G}"
+
+
+def test_persistent_full_size_cfg5_is_bit_identical(swz):
+    a, b = si.config_inputs("cfg5_ragged")
+    base = run_modes(swz, a, b, modes=(2,))[2]
+    pers = run_modes(swz, a, b, modes=(0, 2), persistent=1)
+    assert np.array_equal(pers[0], base) and np.array_equal(pers[2], base)
+    ii, jj = sample_indices(10000, 7000, 256, 256, seed=11, n=1024)
+    assert_within_tolerance(base[ii, jj], gemm_ref.gemm_elems(a, b, ii, jj), "cfg5 persistent samples")

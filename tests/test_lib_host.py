@@ -17,7 +17,8 @@ def test_library_exports_every_declared_entry_point():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(swz_[a-z_]+)\s*\(", header))
     assert declared == {"swz_status_string", "swz_device_info", "swz_pid_map", "swz_pid_map_device", "swz_gemm",
-                        "swz_gemm_ex", "swz_gemm_plan", "swz_copy_bytes"}
+                        "swz_gemm_ex", "swz_gemm_plan", "swz_copy_bytes", "swz_pid_map_persistent",
+                        "swz_pid_map_persistent_device"}
     raw = ctypes.CDLL(swz.binding.LIB_PATH)
     for name in declared:
         assert hasattr(raw, name), name
@@ -103,3 +104,34 @@ def test_gemm_rejects_bad_arguments_before_touching_the_device():
     assert L.swz_gemm_ex(A, B, C, 64, 60, 64, 0, 0, ref, None) == -2          # N % 8
     assert L.swz_gemm_ex(A + 2, B, C, 64, 64, 64, 0, 0, ref, None) == -2      # alignment
     assert L.swz_gemm_ex(A, B, C, 1 << 31, 64, 64, 0, 0, ref, None) == -3
+
+
+def test_persistent_closed_form_equals_constructive_oracle():
+    for gm in range(1, 9):
+        for gn in range(1, 9):
+            for X in (1, 3, 4, 8):
+                for G in (1, 2, 5, 8, 12, 64):
+                    for mode in range(4):
+                        got = swz.pid_map_persistent(gm, gn, X, 3, mode, G).tolist()
+                        assert got == opm.pid_map_persistent(gm, gn, X, 3, mode, G), (gm, gn, X, G, mode)
+    for gm, gn in [(16, 16), (32, 32), (64, 8), (40, 28), (79, 55)]:
+        for mode in range(4):
+            assert swz.pid_map_persistent(gm, gn, 8, 4, mode, 256).tolist() == opm.pid_map_persistent(gm, gn, 8, 4, mode, 256)
+
+
+def test_persistent_error_paths():
+    L = swz.lib
+    out = np.full(64, -7, dtype=np.int32)
+    assert L.swz_pid_map_persistent(4, 4, 8, 4, 0, 0, out.ctypes.data) == -1
+    assert L.swz_pid_map_persistent(4, 4, 8, 4, 0, -3, out.ctypes.data) == -1
+    assert L.swz_pid_map_persistent(4, 4, 8, 4, 6, 8, out.ctypes.data) == -1
+    assert L.swz_pid_map_persistent(4, 4, 8, 4, 0, 8, None) == -1
+    assert (out == -7).all()
+    p = swz.gemm_plan(8192, 8192, 8192, num_xcd=8, persistent=1, num_wg=256)
+    assert (p["persistent"], p["num_wg"]) == (1, 256)
+    p = swz.gemm_plan(512, 512, 512, num_xcd=8, persistent=1, num_wg=256)
+    assert p["num_wg"] == 16                                   # never more workgroups than tiles
+    p = swz.gemm_plan(512, 512, 512, num_xcd=8)
+    assert (p["persistent"], p["num_wg"]) == (0, 0)
+    with pytest.raises(swz.SwzError):
+        swz.gemm_plan(512, 512, 512, num_xcd=8, persistent=2)

@@ -119,3 +119,53 @@ def test_bad_arguments_raise():
     for args in [(0, 4, 8, 4, 0), (4, 0, 8, 4, 0), (4, 4, 0, 4, 1), (4, 4, 8, 0, 2), (4, 4, 8, 4, 4), (4, 4, 8, 4, -1)]:
         with pytest.raises(ValueError):
             opm.pid_map(*args)
+
+
+# ---------------------------------------------------------------------------- persistent launch style
+
+def test_persistent_map_is_the_papers_listing_on_its_own_shape():
+    # the paper's kernel: num_blocks = number of compute units (304 on the part it names), 8 XCDs, and a
+    # tile loop with that stride; pid = (pid % 8) * 38 + pid // 8 for 304 = 8 * 38 workgroups
+    G, X = 304, 8
+    gm, gn = 32, 32
+    rounds = opm.pid_map_persistent(gm, gn, X, 1, opm.MODE_XCD, G)
+    for i, row in enumerate(rounds):
+        for w, t in enumerate(row):
+            pos = paper_printed_swizzle(w, G, X) + i * G
+            assert t == (pos if pos < gm * gn else -1)
+
+
+@pytest.mark.parametrize("gm,gn,X,g,G", [(16, 16, 8, 4, 256), (32, 32, 8, 4, 256), (40, 28, 8, 4, 256), (5, 7, 8, 4, 6),
+                                         (7, 3, 4, 2, 10), (4, 5, 4, 4, 8), (3, 3, 8, 4, 9), (9, 11, 8, 4, 30), (6, 6, 5, 3, 7)])
+def test_persistent_map_invariants(gm, gn, X, g, G):
+    T = gm * gn
+    for mode in range(4):
+        rounds = opm.pid_map_persistent(gm, gn, X, g, mode, G)
+        assert len(rounds) == -(-T // G) and all(len(r) == G for r in rounds)
+        tiles = [t for r in rounds for t in r if t >= 0]
+        assert opm.is_permutation(tiles, T)                       # every tile exactly once
+        order = opm.raster_order(gm, gn, g, mode in (2, 3))
+        pos = {pm * gn + pn: l for l, (pm, pn) in enumerate(order)}
+        for i, row in enumerate(rounds):
+            # a workgroup never skips a round and then works again
+            for w in range(G):
+                if row[w] < 0:
+                    assert all(r[w] < 0 for r in rounds[i:])
+            if mode in (1, 2):
+                # in a full round the tiles of one XCD are one contiguous run of the raster
+                if all(t >= 0 for t in row):
+                    for x in range(min(X, G)):
+                        ps = sorted(pos[row[w]] for w in range(x, G, X))
+                        assert ps == list(range(ps[0], ps[0] + len(ps)))
+        if G >= T:
+            # one round, and then it is the one-workgroup-per-tile map restricted to T workgroups only
+            # when nothing is renumbered
+            assert len(rounds) == 1
+            if mode in (0, 3):
+                assert rounds[0][:T] == opm.pid_map(gm, gn, X, g, mode)
+
+
+def test_persistent_with_one_workgroup_per_tile_equals_the_plain_map():
+    for gm, gn, X, g in [(4, 5, 4, 2), (6, 7, 8, 4), (3, 3, 8, 4)]:
+        for mode in range(4):
+            assert opm.pid_map_persistent(gm, gn, X, g, mode, gm * gn) == [opm.pid_map(gm, gn, X, g, mode)]
