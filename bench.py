@@ -3,8 +3,9 @@
 One "step" is one whole pass of the hot path: a single swz_gemm launch (PID remap, raster
 decode, global->LDS staging, MFMA loop, epilogue) over the 4096^3 workload, inputs resident
 in HBM.  Prints ONE JSON line.  `value` is the throughput of the swizzled mapping (XCD
-renumbering + grouped-M raster); the round-robin and XCD-only mappings, timed the same way in
-the same run, are reported beside it, as is the 8192^3 workload.
+renumbering + grouped-M raster) over exactly --steps timed launches; the round-robin and
+XCD-only mappings and the persistent launch style, timed interleaved in the same run, are
+reported beside it, as are the 8192^3 and the skinny 16384x2048x8192 workloads.
 """
 from __future__ import annotations
 
@@ -59,6 +60,26 @@ def time_mode(swz, torch, a, b, c, mode, steps, warmup, **params):
     return start.elapsed_time(stop) / steps, wall_ms / steps
 
 
+def compare_mappings(swz, torch, a, b, c, variants, per_pass, warmup, flops, passes=5):
+    """Time several mappings interleaved (passes over all of them, median per mapping) after a common
+    warm-up, so that clock ramp-up and drift do not favour whichever is measured last."""
+    def mode_of(name):
+        return swz.MODES[name.replace("persistent_", "")]
+    for name, params in variants:
+        time_mode(swz, torch, a, b, c, mode_of(name), warmup, warmup, **params)
+    samples = {name: [] for name, _ in variants}
+    for _ in range(passes):
+        for name, params in variants:
+            ms, _ = time_mode(swz, torch, a, b, c, mode_of(name), per_pass, 2, **params)
+            samples[name].append(ms)
+    out = {}
+    for name, _ in variants:
+        ms = sorted(samples[name])[passes // 2]
+        t = flops / ms / 1e9
+        out[name] = dict(ms=ms, tflops=t, pct_mfma_peak=100.0 * t / PEAK_BF16_TFLOPS)
+    return out
+
+
 def to_device(torch, np, bits):
     return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
 
@@ -109,14 +130,10 @@ def main():
     def pct(t):
         return 100.0 * t / PEAK_BF16_TFLOPS
 
-    per_mode = {}
-    for name in ("rr", "xcd", "xcd_groupm"):
-        ms, _ = time_mode(swz, torch, a, b, c, swz.MODES[name], max(args.steps // 4, 1), args.warmup)
-        per_mode[name] = dict(ms=ms, tflops=flops / ms / 1e9, pct_mfma_peak=pct(flops / ms / 1e9))
-    # the paper's own launch style (as many workgroups as compute units, tile loop), unswizzled and swizzled
-    for name in ("rr", "xcd_groupm"):
-        ms, _ = time_mode(swz, torch, a, b, c, swz.MODES[name], max(args.steps // 4, 1), args.warmup, persistent=1)
-        per_mode["persistent_" + name] = dict(ms=ms, tflops=flops / ms / 1e9, pct_mfma_peak=pct(flops / ms / 1e9))
+    variants = [("rr", {}), ("xcd", {}), ("xcd_groupm", {}),
+                # the paper's own launch style (as many workgroups as compute units, tile loop)
+                ("persistent_rr", dict(persistent=1)), ("persistent_xcd_groupm", dict(persistent=1))]
+    per_mode = compare_mappings(swz, torch, a, b, c, variants, max(args.steps // 10, 1), args.warmup, flops)
     # the headline run: exactly `steps` timed launches of the swizzled kernel
     ms, wall_ms = time_mode(swz, torch, a, b, c, swz.MODE_XCD_GROUPM, args.steps, args.warmup)
     tflops = flops / ms / 1e9
@@ -156,19 +173,17 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         out["context_vendor_blas_tflops"] = flops / (e0.elapsed_time(e1) / 50) / 1e9
-        # the large square workload, same launch path
-        big = "cfg3_8192"
-        bc = si.CONFIGS[big]
-        a3b, b3b = si.config_inputs(big)
-        a3, b3 = to_device(torch, np, a3b), to_device(torch, np, b3b)
-        c3 = torch.empty((bc["M"], bc["N"]), dtype=torch.bfloat16, device="cuda")
-        f3 = 2.0 * bc["M"] * bc["N"] * bc["K"]
-        extra = {}
-        for name in ("rr", "xcd", "xcd_groupm"):
-            m3, _ = time_mode(swz, torch, a3, b3, c3, swz.MODES[name], 30, 5)
-            extra[name] = dict(ms=m3, tflops=f3 / m3 / 1e9, pct_mfma_peak=pct(f3 / m3 / 1e9))
-        out["other_workloads"] = {big: extra}
-        del a3, b3, c3
+        # the large square workload and the skinny projection-shaped one (where the default dispatch
+        # hurts most), same launch path, same interleaved comparison
+        out["other_workloads"] = {}
+        for other in ("cfg3_8192", "cfg4_skinny"):
+            oc = si.CONFIGS[other]
+            ab, bb = si.config_inputs(other)
+            a3, b3 = to_device(torch, np, ab), to_device(torch, np, bb)
+            c3 = torch.empty((oc["M"], oc["N"]), dtype=torch.bfloat16, device="cuda")
+            f3 = 2.0 * oc["M"] * oc["N"] * oc["K"]
+            out["other_workloads"][other] = compare_mappings(swz, torch, a3, b3, c3, variants, 8, 4, f3)
+            del a3, b3, c3, ab, bb
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(a_bits, b_bits, args.cpu_rows or M)
