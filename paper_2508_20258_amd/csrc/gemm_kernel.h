@@ -5,21 +5,25 @@
 // hardware workgroup id into a tile (pid_decode.h); nothing after that depends on the
 // mapping mode, so every mode produces the same bits.
 //
-// Staging.  Per K step of BK = 32 the workgroup needs an A tile (BM x BK) and a B tile
-// (BK x BN).  They are copied global -> LDS by the memory pipeline itself
-// (global_load_lds_dwordx4: each lane's 16 bytes land at  M0 base + lane*16, no VGPRs
-// involved) into a ring of STAGES buffers, so the loads of steps t+1 .. t+STAGES-1 are in
-// flight while the MFMAs of step t run.  A CU's vector memory path moves 64 bytes per clock,
-// so a 256x256x64 step (64 KB) needs >= 1024 clocks of transfer on top of the L2/HBM latency,
-// against 2048 clocks of MFMA work: one step of look-ahead is not enough, several shorter
-// steps are.  A lane cannot choose where
-// its bytes land, only what it fetches, so the XOR swizzle of the LDS layout is applied on the
-// global-address side: the lane that owns slot p of a row fetches chunk p ^ key(row).
-// Out-of-range chunks (rows >= M, columns >= N, k >= K) are fetched from a 16-byte block of
-// zeros, which keeps every address valid and makes the K tail exact.
+// Staging.  The K loop advances in steps of 32.  Operands are copied global -> LDS by the
+// memory pipeline itself (global_load_lds_dwordx4: each lane's 16 bytes land at
+// M0 base + lane*16, no VGPRs involved) into two rings:
+//   A ring: 3 slots, each a "double" BM x 64 (two K steps), so that a lane group fetches whole
+//           128-byte lines of a row of A; a 32-wide slice would fetch every line as two
+//           64-byte halves, i.e. twice the L2 requests for the same bytes (measured: +2.5 %
+//           time).
+//   B ring: 4 slots, each 32 x BN (rows of B are whole lines already).
+// A CU's vector memory path moves 64 bytes per clock, so a 256x256x64 panel pair (64 KB) needs
+// >= 1024 clocks of transfer on top of the L2/HBM latency against 2048 clocks of MFMA work: the
+// loads run two to three steps ahead of their use.  A lane cannot choose where its bytes land,
+// only what it fetches, so the XOR swizzle of the LDS layout is applied on the global-address
+// side: the lane that owns slot p of a row fetches chunk p ^ key(row).
+// Rows >= M and columns >= N are fetched from clamped, valid addresses (what they bring in only
+// reaches accumulators that are never stored); chunks with k >= K are fetched from a 16-byte
+// block of zeros, which makes the K tail exact.
 //
 // MFMA (v_mfma_f32_16x16x32_bf16, lane l of 64).  Each operand register holds, for one row
-// (or column) index l%16, the 8 consecutive k values 8*(l/16) .. +7 of a 32-wide k-block:
+// (or column) index l%16, the 8 consecutive k values 8*(l/16) .. +7 of a 32-wide K step:
 //   fragment of A: A[m = l%16][k..]   -> one 16-byte LDS read (A is k-contiguous)
 //   fragment of B: B[k..][n = l%16]   -> B is n-contiguous, so it is fetched with two
 //       transposing LDS reads (ds_read_b64_tr_b16): inside each 16-lane group, lane s
@@ -32,20 +36,21 @@
 // flops: with random operands held in registers and no memory traffic the chip sustains
 // about 2.1 PFLOP/s with it against 1.9 PFLOP/s with 32x32x16 (the clock settles higher).
 //
-// Main loop.  While the MFMAs of K step t run, the LDS reads of step t+1 and the global loads
-// of step t+STAGES-1 are issued, one memory instruction per MFMA slot.  One workgroup barrier
-// per step, with no LDS-counter wait attached (the stage that is refilled after it was consumed
-// a whole step earlier).  Steps past the end of K are fetched as zeros, which keeps the loop
-// free of tail cases: before each barrier exactly STAGES-2 steps are outstanding and the wave
-// waits until only STAGES-3 are.
+// Main loop.  While the MFMAs of K step t run, the LDS reads of step t+1 and a fixed share of
+// global loads are issued, one memory instruction per MFMA slot.  One workgroup barrier per
+// step, with no LDS-counter wait attached: a slot is refilled only after the barrier that
+// follows the step which consumed it.  Steps past the end of K are fetched as zeros, which
+// keeps the loop free of tail cases: every step issues the same number of loads and waits until
+// only its predecessor's are outstanding.
 //
 // Epilogue.  Each wave converts its accumulators to bf16 (nearest even), writes them to a
 // wave-private LDS patch and reads them back row-wise, so that global stores are 16 bytes
 // per lane and cover whole 128-byte lines.
 //
 // LDS layouts (16-byte chunks, XOR-swizzled so that the read patterns spread over banks):
-//   A: row r at byte r*64, chunk c (8 k-values) stored in slot c ^ ((r>>2) & 3): the 64 lanes of
-//      a fragment read (16 rows x 4 chunks) then cover one contiguous KiB exactly once.
+//   A: row r at byte r*128, chunk c (8 k-values, c = 0..7 over the double) stored in slot
+//      c ^ ((r>>1) & 7): the 16 lanes that read one chunk index of 16 consecutive rows hit 16
+//      different 16-byte bank groups.
 //   B: row k at byte k*BN*2, chunk c (8 columns) stored in slot c ^ (f(k) << 1) with
 //      f(k) = (k & 3) | ((k>>3 & 1) << 2): the 8 rows a half-wave reads land in 8 different
 //      32-byte bank groups.
@@ -63,63 +68,46 @@ namespace swz {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
-
-// Source of every out-of-range 16-byte chunk.
+// Source of every chunk that lies past the end of K.
 __device__ const u32x4 kZeroChunk = {0u, 0u, 0u, 0u};
 
-template <int BM_, int BN_, int BK_, int STAGES_, int WM_, int WN_>
+constexpr int kStepK = 32;     // K extent of one main-loop step (one 16x16x32 MFMA deep)
+constexpr int kASlots = 3;     // A ring: doubles (two steps each)
+constexpr int kBSlots = 4;     // B ring: single steps
+
+template <int BM_, int BN_, int WM_, int WN_>
 struct GemmShape {
-  static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_, WM = WM_, WN = WN_;
-  static constexpr int KK = BK / 32;               // MFMA k-blocks (32 wide) per K step
+  static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
   static constexpr int NW = WM * WN;               // waves per workgroup
   static constexpr int NT = NW * 64;               // threads per workgroup
   static constexpr int TM = BM / WM / 16;          // 16x16 blocks per wave, rows
   static constexpr int TN = BN / WN / 16;          // 16x16 blocks per wave, columns
-  static constexpr int A_BYTES = BM * BK * 2;
-  static constexpr int B_BYTES = BK * BN * 2;
-  static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-  static constexpr int A_ROW_CHUNKS = BK / 8;      // 16-byte chunks per A row
+  static constexpr int A_SLOT_BYTES = BM * 2 * kStepK * 2;   // BM rows x 64 k
+  static constexpr int B_SLOT_BYTES = kStepK * BN * 2;       // 32 rows x BN
+  static constexpr int A_RING_BYTES = kASlots * A_SLOT_BYTES;
+  static constexpr int RING_BYTES = A_RING_BYTES + kBSlots * B_SLOT_BYTES;
   static constexpr int B_ROW_CHUNKS = BN / 8;      // 16-byte chunks per B row
-  static constexpr int A_LOADS = BM * A_ROW_CHUNKS / NT;   // 16-byte chunks each thread moves per step
-  static constexpr int B_LOADS = BK * B_ROW_CHUNKS / NT;
-  static constexpr int LOADS = A_LOADS + B_LOADS;
+  static constexpr int A_LOADS = BM * 8 / NT;      // 16-byte chunks each thread moves per A double
+  static constexpr int B_LOADS = kStepK * B_ROW_CHUNKS / NT;   // ... per B step
+  static constexpr int LOADS = A_LOADS / 2 + B_LOADS;          // loads each thread issues per step
   // epilogue patch of one wave: (TM*16) rows of (TN*16) bf16, row pitch padded by 16 bytes
   static constexpr int EPI_PITCH = TN * 16 * 2 + 16;
   static constexpr int EPI_WAVE_BYTES = TM * 16 * EPI_PITCH;
   static constexpr int EPI_BYTES = NW * EPI_WAVE_BYTES;
-  static constexpr int LDS_BYTES = STAGES * STAGE_BYTES > EPI_BYTES ? STAGES * STAGE_BYTES : EPI_BYTES;
-  static_assert(BK == 32, "K step");
-  static_assert(STAGES >= 3 && (STAGES - 1) * LOADS < 64, "ring depth must fit the vmcnt counter");
+  static constexpr int LDS_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
   static_assert(BM % (WM * 16) == 0 && BN % (WN * 16) == 0, "wave tiling");
-  static_assert((BM * A_ROW_CHUNKS) % NT == 0 && (BK * B_ROW_CHUNKS) % NT == 0, "load tiling");
+  static_assert((BM * 8) % NT == 0 && (kStepK * B_ROW_CHUNKS) % NT == 0 && A_LOADS % 2 == 0, "load tiling");
+  static_assert(A_LOADS / 2 == B_LOADS, "A and B loads alternate within a step");
   static_assert(TN * 16 * 2 / 16 <= 64 && 64 % (TN * 16 * 2 / 16) == 0, "epilogue row must divide a wave");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS per workgroup");
 };
 
-template <int BK>
-__device__ __forceinline__ int a_slot(int row, int chunk) {
-  return chunk ^ ((row >> 2) & 3);
-}
+__device__ __forceinline__ int a_slot(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
 
-template <int BK>
-__device__ __forceinline__ int a_lds_off(int row, int chunk) {
-  return row * (BK * 2) + (a_slot<BK>(row, chunk) << 4);
-}
-
-// Workgroup barrier alone: no counter waits attached (the kernel states the ones it needs), and
-// the memory clobber keeps the compiler from moving LDS accesses across it.
-__device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" ::: "memory"); }
-
-// s_waitcnt that waits only for the vector-memory counter to drop to n.
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  __builtin_amdgcn_s_waitcnt((N & 0xF) | 0x0070 | 0x0F00 | ((N >> 4) << 14));
-}
+__device__ __forceinline__ int a_lds_off(int row, int chunk) { return row * 128 + (a_slot(row, chunk) << 4); }
 
 __device__ __forceinline__ int b_key(int krow) { return ((krow & 3) | (((krow >> 3) & 1) << 2)) << 1; }
 
@@ -132,10 +120,20 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const unsigned char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
 }
 
+// Workgroup barrier alone: no counter waits attached (the kernel states the ones it needs), and
+// the memory clobber keeps the compiler from moving LDS accesses across it.
+__device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// s_waitcnt that waits only for the vector-memory counter to drop to n.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | 0x0070 | 0x0F00 | ((N >> 4) << 14));
+}
+
 // 16 bytes per lane, global -> LDS at (wave-uniform) LDS byte address lds_base + lane*16.
 // Written as inline assembly on purpose: the compiler then keeps no book on these loads, so it
-// does not guard later LDS reads of the *other* stage with a conservative vmcnt(0); the kernel
-// waits for them itself (s_waitcnt vmcnt(0) before the barrier that publishes a stage).
+// does not guard later LDS reads of *other* ring slots with a conservative vmcnt(0); the kernel
+// waits for them itself (s_waitcnt vmcnt before the barrier that publishes a slot).
 __device__ __forceinline__ void load_to_lds(const void* gptr, uint32_t lds_base) {
   const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(lds_base);   // wave-uniform by construction
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory", "m0");
@@ -154,7 +152,7 @@ template <class S>
 __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
                                           uint16_t* __restrict__ C, int M, int N, int K, int pm, int pn,
                                           unsigned char* smem) {
-  constexpr int BM = S::BM, BN = S::BN, BK = S::BK, KK = S::KK, TM = S::TM, TN = S::TN, STAGES = S::STAGES;
+  constexpr int BM = S::BM, BN = S::BN, TM = S::TM, TN = S::TN;
   const int m0 = pm * BM;
   const int n0 = pn * BN;
 
@@ -164,19 +162,17 @@ __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const 
   const int wm = wave / S::WN;
   const int wn = wave % S::WN;
 
-  // ---- global -> LDS staging: which chunk of the tile this lane fetches for each of its loads ----
-  // Load i of wave w fills LDS bytes [(w*LOADS + i)*1024, +1024) of the A (resp. B) region.
-  // A lane's source is  tile base (uniform, advances with the K step) + a 32-bit byte offset that
-  // never changes.  Rows >= M and columns >= N are clamped to the last valid row / 8-column chunk:
-  // whatever they bring in only reaches accumulators of C rows >= M or columns >= N, which are never
-  // stored.  Only a K step that crosses the end of K needs zeros, and takes the predicated path.
+  // ---- global -> LDS staging: which chunk this lane fetches for each of its loads ----
+  // A load i (0 .. A_LOADS-1) of wave w fills LDS bytes [(w*A_LOADS + i)*1024, +1024) of an A slot:
+  // 8 rows x 128 bytes.  B load i fills [(w*B_LOADS + i)*1024, +1024) of a B slot: 2 rows x 512 bytes.
+  // A lane's source is  tile base (uniform, advances with k) + a 32-bit byte offset that never changes.
   uint32_t a_off[S::A_LOADS], b_off[S::B_LOADS];
-  int a_k[S::A_LOADS], b_k[S::B_LOADS];       // k offset of the chunk inside a K step
+  int a_k[S::A_LOADS], b_k[S::B_LOADS];       // k offset of the chunk inside its double / step
 #pragma unroll
   for (int i = 0; i < S::A_LOADS; ++i) {
     const int q = (wave * S::A_LOADS + i) * 64 + lane;
-    const int row = q / S::A_ROW_CHUNKS, slot = q % S::A_ROW_CHUNKS;
-    const int c = a_slot<BK>(row, slot);       // XOR with a key is its own inverse
+    const int row = q >> 3, slot = q & 7;
+    const int c = a_slot(row, slot);           // XOR with a key is its own inverse
     const int r = (m0 + row < M) ? row : (M - 1 - m0);
     a_k[i] = c * 8;
     a_off[i] = (uint32_t)r * (uint32_t)K * 2u + (uint32_t)c * 16u;
@@ -192,26 +188,29 @@ __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const 
   }
   const unsigned char* a_tile = reinterpret_cast<const unsigned char*>(A + (size_t)m0 * K);
   const unsigned char* b_tile = reinterpret_cast<const unsigned char*>(B + n0);
-  const size_t a_step = (size_t)BK * 2;           // bytes per K step along a row of A
-  const size_t b_step = (size_t)BK * N * 2;       // bytes per K step down the rows of B
+  const size_t a_dbl = (size_t)2 * kStepK * 2;        // bytes per A double along a row of A
+  const size_t b_step = (size_t)kStepK * N * 2;       // bytes per K step down the rows of B
   const unsigned char* zero = reinterpret_cast<const unsigned char*>(&kZeroChunk);
-  const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;   // LDS byte address of the ring
+  const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;   // LDS byte address of the rings
 
-  // Load number idx (0 .. LOADS-1) of K step kt into `stage`; A and B loads alternate.
-  // full = the whole step lies inside K (uniform): no per-lane work at all.
-  auto issue_load = [&](int kt, int stage, int idx, auto full) __attribute__((always_inline)) {
-    const uint32_t sA = smem_addr + stage * S::STAGE_BYTES;
-    const uint32_t sB = sA + S::A_BYTES;
-    const int i = idx >> 1;
-    const bool is_a = (idx & 1) == 0;
-    const unsigned char* base = is_a ? a_tile + kt * a_step : b_tile + kt * b_step;
-    const uint32_t off = is_a ? a_off[i] : b_off[i];
-    const uint32_t dst = is_a ? sA + (wave * S::A_LOADS + i) * 1024 : sB + (wave * S::B_LOADS + i) * 1024;
+  // Load i of A double d into its ring slot.  full = the double lies wholly inside K (uniform).
+  auto load_a = [&](int d, int i, auto full) __attribute__((always_inline)) {
+    const unsigned char* base = a_tile + d * a_dbl;
+    const uint32_t dst = smem_addr + (d % kASlots) * S::A_SLOT_BYTES + (wave * S::A_LOADS + i) * 1024;
     if constexpr (decltype(full)::value) {
-      load_to_lds_base_off(base, off, dst);
+      load_to_lds_base_off(base, a_off[i], dst);
     } else {
-      const bool ok = kt * BK + (is_a ? a_k[i] : b_k[i]) < K;
-      load_to_lds(ok ? base + off : zero, dst);
+      load_to_lds(d * 2 * kStepK + a_k[i] < K ? base + a_off[i] : zero, dst);
+    }
+  };
+  // Load i of B step t into its ring slot.
+  auto load_b = [&](int t, int i, auto full) __attribute__((always_inline)) {
+    const unsigned char* base = b_tile + t * b_step;
+    const uint32_t dst = smem_addr + S::A_RING_BYTES + (t % kBSlots) * S::B_SLOT_BYTES + (wave * S::B_LOADS + i) * 1024;
+    if constexpr (decltype(full)::value) {
+      load_to_lds_base_off(base, b_off[i], dst);
+    } else {
+      load_to_lds(t * kStepK + b_k[i] < K ? base + b_off[i] : zero, dst);
     }
   };
   constexpr std::true_type kFull{};
@@ -227,7 +226,7 @@ __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const 
 
   // lane-constant parts of the fragment addresses
   const int a_row0 = wm * (TM * 16) + (lane & 15);          // + 16*bi
-  const int a_kc0 = lane >> 4;                              // 16-byte chunk index along k
+  const int a_kc0 = lane >> 4;                              // 16-byte chunk index along k (+4 for odd steps)
   const int b_krow0 = 8 * (lane >> 4) + ((lane & 15) >> 2); // (+4 for the upper half)
   const int b_col0 = wn * (TN * 16) + 4 * (lane & 3);       // + 16*bj
 
@@ -238,15 +237,16 @@ __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const 
   bf16x8 af[TM];
   s16x4 bq[2][TN][2];
   constexpr int NM = TM * TN;             // MFMAs per step
-  auto read_a = [&](int stage, int bi) __attribute__((always_inline)) {
-    const unsigned char* sA = smem + stage * S::STAGE_BYTES;
-    af[bi] = *reinterpret_cast<const bf16x8*>(sA + a_lds_off<BK>(a_row0 + 16 * bi, a_kc0));
+  // A fragment bi of K step t (t = 2*double + half).
+  auto read_a = [&](int a_slot_idx, int half, int bi) __attribute__((always_inline)) {
+    const unsigned char* sA = smem + a_slot_idx * S::A_SLOT_BYTES;
+    af[bi] = *reinterpret_cast<const bf16x8*>(sA + a_lds_off(a_row0 + 16 * bi, a_kc0 + 4 * half));
   };
-  auto read_b = [&](int buf, int stage, int bj, int half) __attribute__((always_inline)) {
-    const unsigned char* sB = smem + stage * S::STAGE_BYTES + S::A_BYTES;
+  auto read_b = [&](int buf, int b_slot_idx, int bj, int hi) __attribute__((always_inline)) {
+    const unsigned char* sB = smem + S::A_RING_BYTES + b_slot_idx * S::B_SLOT_BYTES;
     const int col = b_col0 + 16 * bj;
-    const int kr = b_krow0 + 4 * half;
-    bq[buf][bj][half] = lds_read_tr16(sB + b_lds_off<BN>(kr, col >> 3) + (col & 7) * 2);
+    const int kr = b_krow0 + 4 * hi;
+    bq[buf][bj][hi] = lds_read_tr16(sB + b_lds_off<BN>(kr, col >> 3) + (col & 7) * 2);
   };
   auto mfma = [&](int buf, int bi, int bj) __attribute__((always_inline)) {
     const bf16x8 b = __builtin_bit_cast(bf16x8, __builtin_shufflevector(bq[buf][bj][0], bq[buf][bj][1], 0, 1, 2, 3, 4, 5, 6, 7));
@@ -256,39 +256,59 @@ __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const 
   // One K step, issued as NM slots.  Slot i = MFMA (bi, bj) on the fragments of the current
   // step, then at most one LDS read for the next step (the B halves in the first 2*TN slots,
   // the A fragment of row-block bi after that block's last MFMA), then, in the middle of every
-  // (NM/LOADS)-th run of slots, one global->LDS load of K step ld_kt.  Nothing moves across slot
-  // boundaries, so memory instructions are fed to their queues at the pace of the MFMA pipe
-  // instead of in bursts that would block the (in-order) wave.
+  // (NM/LOADS)-th run of slots, one global->LDS load.  Nothing moves across slot boundaries, so
+  // memory instructions are fed to their queues at the pace of the MFMA pipe instead of in
+  // bursts that would block the (in-order) wave.
+  //   HALF   = t & 1 (compile time): fragment buffer of this step's B, and which half of the
+  //            A double the NEXT step reads (1 - HALF).
+  //   loads  : A loads [HALF*A_LOADS/2, +A_LOADS/2) of double ld_d, B loads of step ld_t.
   constexpr int SEG = NM / S::LOADS;
-  static_assert(NM % S::LOADS == 0 && S::A_LOADS == S::B_LOADS && 2 * TN <= NM, "slot schedule");
-  auto kblock = [&](int cur, int rd_stage, int ld_kt, int ld_stage, auto full) __attribute__((always_inline)) {
+  static_assert(NM % S::LOADS == 0 && 2 * TN <= NM, "slot schedule");
+  auto kblock = [&](auto half_tag, int rd_a_slot, int rd_b_slot, int ld_d, int ld_t, auto full) __attribute__((always_inline)) {
+    constexpr int HALF = decltype(half_tag)::value;
 #pragma unroll
     for (int i = 0; i < NM; ++i) {
       const int bi = i / TN, bj = i % TN;
-      mfma(cur, bi, bj);
-      if (i < 2 * TN) read_b(cur ^ 1, rd_stage, i / 2, i % 2);
-      if (bj == TN - 1) read_a(rd_stage, bi);
-      if (i % SEG == SEG / 2) issue_load(ld_kt, ld_stage, i / SEG, full);
+      mfma(HALF, bi, bj);
+      if (i < 2 * TN) read_b(HALF ^ 1, rd_b_slot, i / 2, i % 2);
+      if (bj == TN - 1) read_a(rd_a_slot, HALF ^ 1, bi);
+      if (i % SEG == SEG / 2) {
+        const int l = i / SEG;                       // 0 .. LOADS-1: A, B, A, B, ...
+        if ((l & 1) == 0) load_a(ld_d, HALF * (S::A_LOADS / 2) + (l >> 1), full);
+        else load_b(ld_t, l >> 1, full);
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
 
-  // K step t lives in stage t%STAGES.  During step t a wave issues the MFMAs of step t, the LDS
-  // reads of step t+1, and the global loads of step t+STAGES-1 into the stage of step t-1.
-  //   * reads of step t+1 need that step landed for everybody: each wave waits for its own share
-  //     (vmcnt) and then meets the others at the barrier that opens step t;
-  //   * the refill overwrites the stage of step t-1: every wave consumed its fragments of step t-1
-  //     in the MFMAs it issued before arriving at the same barrier, so those reads have completed
-  //     and the barrier needs no wait on the LDS counter.
-  // Two steps per loop trip keep the fragment-buffer index a compile-time constant; an odd step
-  // count just processes one more step of zeros.
-  static_assert(KK == 1, "one 32-wide k-block per K step");
-  const int KT = (K + BK - 1) / BK;
+  // Step t reads A from double t/2 (half t&1) and B from B slot t%4.  During step t a wave issues
+  // the MFMAs of step t, the LDS reads of step t+1, and its share of loads: half of A double
+  // t/2 + 2 (into the slot of double t/2 - 1) and B step t+3 (into the slot of step t-1).
+  //   * the reads of step t+1 need its data landed for everybody: each wave waits until only the
+  //     loads of the step before are outstanding (everything older has landed, which covers B step
+  //     t+1 and A double (t+1)/2, both issued by step t-2 at the latest) and then meets the others
+  //     at the barrier that opens step t;
+  //   * the refills overwrite slots whose last reader was step t-1: every wave consumed those
+  //     fragments in the MFMAs it issued before arriving at the same barrier, so the reads have
+  //     completed and the barrier needs no wait on the LDS counter.
+  // Two steps per loop trip keep the half index a compile-time constant; an odd step count just
+  // processes one more step of zeros.
+  const int KT = (K + kStepK - 1) / kStepK;
+  // prologue: A doubles 0 and 1, B steps 0 .. 2 (what steps 0 and 1 do not fetch themselves), in an
+  // order that leaves as the most recent LOADS loads only things step 0 does not read (the second
+  // half of A double 1 and B step 2): the wait at the barrier of step 0 then covers B step 1.
+  static_assert(kBSlots == 4 && kASlots == 3, "prologue order is written for these ring depths");
 #pragma unroll
-  for (int t = 0; t < STAGES - 1; ++t)
+  for (int i = 0; i < S::A_LOADS; ++i) load_a(0, i, kTail);
 #pragma unroll
-    for (int l = 0; l < S::LOADS; ++l) issue_load(t, t, l, kTail);   // steps past K arrive as zeros
-  wait_vmcnt<(STAGES - 2) * S::LOADS>();                         // step 0 has landed (this wave's part)
+  for (int i = 0; i < S::B_LOADS; ++i) load_b(0, i, kTail);
+#pragma unroll
+  for (int i = 0; i < S::B_LOADS; ++i) load_b(1, i, kTail);
+#pragma unroll
+  for (int i = 0; i < S::A_LOADS; ++i) load_a(1, i, kTail);
+#pragma unroll
+  for (int i = 0; i < S::B_LOADS; ++i) load_b(2, i, kTail);
+  wait_vmcnt<S::A_LOADS + (kBSlots - 2) * S::B_LOADS>();          // A double 0 and B step 0 have landed (this wave's part)
   __syncthreads();                                               // ... and everybody else's
 #pragma unroll
   for (int bj = 0; bj < TN; ++bj) {
@@ -296,28 +316,25 @@ __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const 
     read_b(0, 0, bj, 1);
   }
 #pragma unroll
-  for (int bi = 0; bi < TM; ++bi) read_a(0, bi);
+  for (int bi = 0; bi < TM; ++bi) read_a(0, 0, bi);
 
-  int stage = 0;                       // stage of step kt
-  int freed = STAGES - 1;              // stage of step kt-1, refilled during step kt
-  auto step = [&](int kt, int cur, auto full) __attribute__((always_inline)) {
-    wait_vmcnt<(STAGES - 3) * S::LOADS>();   // step kt+1 has landed (this wave's part)
+  auto step_pair = [&](int t, auto full) __attribute__((always_inline)) {   // t even
+    const int d = t >> 1;
+    // step t: next step (t+1) reads the upper half of the same double
+    wait_vmcnt<S::LOADS>();
     block_barrier();
-    const int next = (stage + 1 == STAGES) ? 0 : stage + 1;
-    kblock(cur, next, kt + STAGES - 1, freed, full);
-    freed = stage;
-    stage = next;
+    kblock(std::integral_constant<int, 0>{}, d % kASlots, (t + 1) % kBSlots, d + 2, t + 3, full);
+    // step t+1: next step (t+2) reads the lower half of the next double
+    wait_vmcnt<S::LOADS>();
+    block_barrier();
+    kblock(std::integral_constant<int, 1>{}, (d + 1) % kASlots, (t + 2) % kBSlots, d + 2, t + 4, full);
   };
-  const int full_steps = K / BK;       // steps 0 .. full_steps-1 lie wholly inside K
-  int kt = 0;
-  for (; kt + STAGES < full_steps; kt += 2) {   // both refills of this trip fetch whole steps
-    step(kt, 0, kFull);
-    step(kt + 1, 1, kFull);
-  }
-  for (; kt < KT; kt += 2) {
-    step(kt, 0, kTail);
-    step(kt + 1, 1, kTail);
-  }
+  // steps 0 .. full_steps-1 lie wholly inside K; a trip is "full" if everything it fetches does
+  // (A double t/2+2 = steps t+4, t+5; B steps t+3, t+4)
+  const int full_steps = K / kStepK;
+  int t = 0;
+  for (; t + 6 <= full_steps; t += 2) step_pair(t, kFull);
+  for (; t < KT; t += 2) step_pair(t, kTail);
 
   // ---- epilogue: fp32 -> bf16 (nearest even), transpose through a wave-private LDS patch ----
   wait_vmcnt<0>();   // the zero-filled look-ahead steps have landed too
