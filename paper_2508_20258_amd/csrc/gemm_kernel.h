@@ -362,7 +362,8 @@ __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const 
     const u32x4 v = *reinterpret_cast<const u32x4*>(patch + r * S::EPI_PITCH + ec * 16);
     const int row = m0 + wm * (TM * 16) + r;
     const int col = n0 + wn * (TN * 16) + ec * 8;
-    if (row < M && col < N) *reinterpret_cast<u32x4*>(C + (size_t)row * N + col) = v;
+    // C is written once and not read again by this kernel: streaming (non-temporal) stores
+    if (row < M && col < N) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(C + (size_t)row * N + col));
   }
 }
 
