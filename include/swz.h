@@ -125,6 +125,20 @@ int swz_gemm_ex(const void* A, const void* B, void* C, int64_t M, int64_t N, int
 int swz_gemm_plan(int64_t M, int64_t N, int64_t K, const swz_params* params, swz_params* resolved,
                   int* grid_m, int* grid_n);
 
+/* out (N x M) = transpose of in (M x N), 16-bit elements moved verbatim, both row-major and dense
+ * (the paper's transpose case study, its largest win from XCD swizzling: Results; Appendix "Case
+ * Study: Other Swizzling Pattern Examples").  One workgroup per tile x tile block of `in`; the tile
+ * grid is ceil(M/tile) x ceil(N/tile) and hardware workgroup ids are turned into tiles exactly as
+ * swz_pid_map does for that grid (`mode`, params->group_m, params->num_xcd; other fields ignored).
+ *   in, out : caller-owned DEVICE pointers, 16-byte aligned, must not overlap.
+ *   tile    : 64 (row segments are whole 128-byte lines) or 32 (half lines, shared between
+ *             neighbouring tiles: the case where the mapping decides the L2 hit rate).
+ * Asynchronous on `stream`; never allocates or synchronises.
+ * Errors: INVALID_ARG (null, M/N < 1, unknown mode), UNSUPPORTED (elem_bytes != 2, tile not 32/64,
+ * M or N not a multiple of 8, misaligned pointer), OVERFLOW, HIP. */
+int swz_transpose(const void* in, void* out, int64_t M, int64_t N, int elem_bytes, int tile, int mode,
+                  const swz_params* params, hipStream_t stream);
+
 /* Measurement aid, not part of the GEMM path: a plain streaming copy of `bytes` bytes
  * (reads `bytes`, writes `bytes`; both DEVICE pointers 16-byte aligned, bytes a multiple of
  * 16, buffers must not overlap).  The profiling harness scales the profiler's HBM byte

@@ -17,7 +17,7 @@ MODES = {"rr": MODE_RR, "xcd": MODE_XCD, "xcd_groupm": MODE_XCD_GROUPM, "groupm"
 DTYPE_BF16 = 0
 
 EXPORTS = ("swz_status_string", "swz_device_info", "swz_pid_map", "swz_pid_map_device", "swz_gemm", "swz_gemm_ex",
-           "swz_gemm_plan", "swz_copy_bytes", "swz_pid_map_persistent", "swz_pid_map_persistent_device")
+           "swz_gemm_plan", "swz_copy_bytes", "swz_pid_map_persistent", "swz_pid_map_persistent_device", "swz_transpose")
 
 
 class SwzParams(ctypes.Structure):
@@ -67,6 +67,7 @@ def _load() -> ctypes.CDLL:
     L.swz_gemm_ex.argtypes = [vp, vp, vp, i64, i64, i64, i, i, pp, vp]
     L.swz_gemm_plan.argtypes = [i64, i64, i64, pp, pp, ip, ip]
     L.swz_copy_bytes.argtypes = [vp, vp, i64, vp]
+    L.swz_transpose.argtypes = [vp, vp, i64, i64, i, i, i, pp, vp]
     L.swz_pid_map_persistent.argtypes = [i, i, i, i, i, i, vp]
     L.swz_pid_map_persistent_device.argtypes = [i, i, i, i, i, i, vp, vp, vp]
     for name in EXPORTS:
@@ -190,3 +191,17 @@ def pid_map_persistent_device(grid_m: int, grid_n: int, num_xcd: int, group_m: i
                                              tile.data_ptr(), xcc.data_ptr(), _stream_handle(stream)),
            "swz_pid_map_persistent_device")
     return tile, xcc
+
+
+def transpose(x, out=None, tile: int = 64, mode: int = MODE_XCD_GROUPM, stream=None, **params):
+    """out (N x M) = x (M x N) transposed on the GPU through swz_transpose; 16-bit element tensors."""
+    import torch
+    assert x.is_cuda and x.is_contiguous() and x.dim() == 2 and x.element_size() == 2
+    M, N = x.shape
+    if out is None:
+        out = torch.empty((N, M), dtype=x.dtype, device=x.device)
+    assert out.is_cuda and out.is_contiguous() and tuple(out.shape) == (N, M) and out.dtype == x.dtype
+    p = _params(**params)
+    _check(lib.swz_transpose(x.data_ptr(), out.data_ptr(), M, N, 2, int(tile), int(mode), ctypes.byref(p),
+                             _stream_handle(stream)), "swz_transpose")
+    return out

@@ -8,6 +8,7 @@
 #include "../../include/swz.h"
 #include "gemm_kernel.h"
 #include "pid_decode.h"
+#include "transpose_kernel.h"
 
 namespace {
 
@@ -122,6 +123,21 @@ int resolve_plan(int64_t M, int64_t N, int64_t K, const swz_params* p, swz_param
   return SWZ_OK;
 }
 
+template <int TILE>
+int launch_transpose(const void* in, void* out, int M, int N, int gm, int gn, int num_xcd, int group_m, int mode,
+                     hipStream_t stream) {
+  const dim3 grid((unsigned)(gm * gn)), block(256);
+  auto* i = static_cast<const uint16_t*>(in);
+  auto* o = static_cast<uint16_t*>(out);
+  switch (mode) {
+    case SWZ_MODE_RR: hipLaunchKernelGGL((swz::transpose16_kernel<TILE, kModeRR>), grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m); break;
+    case SWZ_MODE_XCD: hipLaunchKernelGGL((swz::transpose16_kernel<TILE, kModeXcd>), grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m); break;
+    case SWZ_MODE_XCD_GROUPM: hipLaunchKernelGGL((swz::transpose16_kernel<TILE, kModeXcdGroupM>), grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m); break;
+    case SWZ_MODE_GROUPM: hipLaunchKernelGGL((swz::transpose16_kernel<TILE, kModeGroupM>), grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m); break;
+    default: return SWZ_ERR_INVALID_ARG;
+  }
+  return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
+}
 }  // namespace
 
 extern "C" {
@@ -203,6 +219,33 @@ int swz_pid_map_persistent_device(int grid_m, int grid_n, int num_xcd, int group
   hipLaunchKernelGGL(swz::pid_map_persistent_kernel, dim3((unsigned)num_wg), dim3(64), 0, stream, grid_m, grid_n,
                      num_xcd, group_m, mode, (int)rounds, d_tile, d_xcc);
   return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
+}
+
+int swz_transpose(const void* in, void* out, int64_t M, int64_t N, int elem_bytes, int tile, int mode,
+                  const swz_params* params, hipStream_t stream) {
+  if (in == nullptr || out == nullptr || M < 1 || N < 1 || !valid_mode(mode)) return SWZ_ERR_INVALID_ARG;
+  const int64_t lim = (int64_t)1 << 31;
+  if (M >= lim || N >= lim) return SWZ_ERR_OVERFLOW;
+  if (elem_bytes != 2 || (tile != 32 && tile != 64) || (M % 8) != 0 || (N % 8) != 0) return SWZ_ERR_UNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) return SWZ_ERR_UNSUPPORTED;
+  int group_m = 4, num_xcd = 0;
+  if (params != nullptr) {
+    if (params->group_m < 0 || params->num_xcd < 0) return SWZ_ERR_INVALID_ARG;
+    if (params->group_m > 0) group_m = params->group_m;
+    num_xcd = params->num_xcd;
+  }
+  if (num_xcd == 0) {
+    DeviceFacts f;
+    const int st = query_device(&f);
+    if (st != SWZ_OK) return st;
+    num_xcd = f.num_xcd;
+  }
+  const int64_t gm = (M + tile - 1) / tile, gn = (N + tile - 1) / tile;
+  if (gm * gn >= lim) return SWZ_ERR_OVERFLOW;
+  const int st = check_map_args((int)gm, (int)gn, num_xcd, &group_m, mode);
+  if (st != SWZ_OK) return st;
+  return tile == 64 ? launch_transpose<64>(in, out, (int)M, (int)N, (int)gm, (int)gn, num_xcd, group_m, mode, stream)
+                    : launch_transpose<32>(in, out, (int)M, (int)N, (int)gm, (int)gn, num_xcd, group_m, mode, stream);
 }
 
 int swz_copy_bytes(const void* src, void* dst, int64_t bytes, hipStream_t stream) {

@@ -1,0 +1,96 @@
+// Tiled 16-bit matrix transpose with a remapped program id:  out (N x M) = in (M x N)^T, both
+// row-major (SwizzlePerf, Results and Appendix "Case Study: Other Swizzling Pattern Examples":
+// the transpose kernel is the paper's largest win from XCD swizzling).
+//
+// One workgroup (256 threads) moves one TILE x TILE block: rows of `in` are read as 16-byte
+// chunks into LDS, and read back with the transposing LDS read of gfx950 (ds_read_b64_tr_b16:
+// inside a 16-lane group, lane s supplies 4 consecutive elements of row s/4 and lane i receives
+// rows 0..3 of column i), so a lane ends up with 8 consecutive elements of one row of `out` and
+// stores them as 16 bytes.  The kernel is bound by HBM: 4*M*N bytes per launch.
+//
+// TILE = 64: every row segment read or written is one whole 128-byte line, so tiles share no
+//            lines and the mapping of tiles to XCDs cannot change the L2 hit rate.
+// TILE = 32: row segments are half lines; horizontally adjacent tiles share the lines they read
+//            and vertically adjacent tiles the lines they write.  This is the situation in which
+//            co-locating neighbouring tiles on one XCD pays, and it is kept to show exactly that.
+//
+// LDS layout: row r at byte r*(TILE*2), 16-byte chunk c in slot c ^ key(r) (same idea as the
+// GEMM's B panel; TILE*2/16 slots per row).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pid_decode.h"
+
+namespace swz {
+
+typedef __attribute__((ext_vector_type(4))) short t_s16x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t t_u32x4;
+
+template <int TILE>
+__device__ __forceinline__ int tr_key(int row) {
+  // the 16 lanes of a transposing read take 4 consecutive rows x 32 bytes (a chunk pair): give
+  // those rows different chunk pairs where the row has room for it
+  return TILE == 64 ? (row & 3) << 1 : (row & 1) << 1;
+}
+
+template <int TILE, int MODE>
+__global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t* __restrict__ in, uint16_t* __restrict__ out,
+                                                          int M, int N, int grid_m, int grid_n, int num_xcd,
+                                                          int group_m) {
+  constexpr int ROW_BYTES = TILE * 2;
+  constexpr int SLOTS = ROW_BYTES / 16;                  // 16-byte chunks per tile row
+  constexpr int CHUNKS = TILE * SLOTS;                   // chunks per tile
+  constexpr int PER_THREAD = CHUNKS / 256 > 0 ? CHUNKS / 256 : 1;
+  __shared__ __attribute__((aligned(16))) unsigned char tile[TILE * ROW_BYTES];
+
+  int pm, pn;
+  swz_decode_tile((int)blockIdx.x, grid_m, grid_n, num_xcd, group_m, MODE, &pm, &pn);
+  const int m0 = pm * TILE, n0 = pn * TILE;
+  const int tid = threadIdx.x;
+
+  // ---- in -> LDS: row-contiguous 16-byte chunks (columns are whole chunks: N % 8 == 0) ----
+#pragma unroll
+  for (int i = 0; i < PER_THREAD; ++i) {
+    const int q = tid + 256 * i;
+    if (q < CHUNKS) {
+      const int r = q / SLOTS, c = q % SLOTS;
+      t_u32x4 v = {0u, 0u, 0u, 0u};
+      if (m0 + r < M && n0 + c * 8 < N) v = *reinterpret_cast<const t_u32x4*>(in + (size_t)(m0 + r) * N + n0 + c * 8);
+      *reinterpret_cast<t_u32x4*>(tile + r * ROW_BYTES + ((c ^ tr_key<TILE>(r)) << 4)) = v;
+    }
+  }
+  __syncthreads();
+
+  // ---- LDS -> out: a wave-instruction covers 16 columns (rows of out) x 32 rows of the tile ----
+  // lane: i = lane%16 -> column, g = lane/16 -> 8-row block; two transposing reads give rows 8g..8g+7
+  const int lane = tid & 63, wave = tid >> 6;
+  const int i = lane & 15, g = lane >> 4;
+  constexpr int COL_BLOCKS = TILE / 16;                  // 16-column blocks
+  constexpr int ROW_BLOCKS = TILE / 32;                  // 32-row blocks
+  constexpr int UNITS = COL_BLOCKS * ROW_BLOCKS;         // wave-level units of work: 8 (TILE 64) or 2 (TILE 32)
+#pragma unroll
+  for (int u = wave; u < UNITS; u += 4) {
+    const int cb = u % COL_BLOCKS, rb = u / COL_BLOCKS;
+    const int row = 32 * rb + 8 * g + (i >> 2);          // the row whose 4 elements this lane supplies (+4 for the second read)
+    const int col = 16 * cb + 4 * (i & 3);
+    const unsigned char* p0 = tile + row * ROW_BYTES + (((col >> 3) ^ tr_key<TILE>(row)) << 4) + (col & 7) * 2;
+    const unsigned char* p1 = tile + (row + 4) * ROW_BYTES + (((col >> 3) ^ tr_key<TILE>(row + 4)) << 4) + (col & 7) * 2;
+    const t_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) t_s16x4*)p0);
+    const t_s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) t_s16x4*)p1);
+    // lane now holds in[m0 + 32rb + 8g .. +7][n0 + 16cb + i]  =  out[n0 + 16cb + i][m0 + 32rb + 8g .. +7]
+    const int on = n0 + 16 * cb + i;
+    const int om = m0 + 32 * rb + 8 * g;
+    if (on < N && om < M) {                              // M % 8 == 0: the 8 elements are in or out together
+      t_u32x4 v;
+      v[0] = (uint32_t)(uint16_t)lo[0] | ((uint32_t)(uint16_t)lo[1] << 16);
+      v[1] = (uint32_t)(uint16_t)lo[2] | ((uint32_t)(uint16_t)lo[3] << 16);
+      v[2] = (uint32_t)(uint16_t)hi[0] | ((uint32_t)(uint16_t)hi[1] << 16);
+      v[3] = (uint32_t)(uint16_t)hi[2] | ((uint32_t)(uint16_t)hi[3] << 16);
+      *reinterpret_cast<t_u32x4*>(out + (size_t)on * M + om) = v;
+    }
+  }
+}
+
+}  // namespace swz

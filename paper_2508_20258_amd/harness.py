@@ -3,6 +3,7 @@ reader that turns rocprofv3's CSV output into the summaries kept with the measur
 
     python -m paper_2508_20258_amd.harness run --workload cfg2_4096 --mode xcd_groupm --launches 10
     python -m paper_2508_20258_amd.harness copy --mib 1024 --launches 3
+    python -m paper_2508_20258_amd.harness transpose --m 16384 --n 16384 --tile 32 --mode rr
     python -m paper_2508_20258_amd.harness summarize <rocprofv3 output dir>
     python -m paper_2508_20258_amd.harness rank --workload cfg4_skinny
 
@@ -111,6 +112,28 @@ def cmd_rank(args):
     if good:
         best = sorted(good, key=lambda r: (-round(r["l2_hit_pct"], 1), r["us_per_launch"]))[0]
         print("best validated candidate: " + json.dumps(best))
+
+
+def cmd_transpose(args):
+    import torch
+
+    import paper_2508_20258_amd as swz
+    torch.manual_seed(0)
+    x = torch.randint(-32768, 32767, (args.m, args.n), dtype=torch.int16, device="cuda").view(torch.bfloat16)
+    out = torch.empty((args.n, args.m), dtype=torch.bfloat16, device="cuda")
+    mode = swz.MODES[args.mode]
+    swz.transpose(x, out, tile=args.tile, mode=mode)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(max(args.launches - 1, 1)):
+        swz.transpose(x, out, tile=args.tile, mode=mode)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / max(args.launches - 1, 1)
+    gbs = 4.0 * args.m * args.n / (us * 1e-6) / 1e9
+    print(f"ran {args.launches} transposes {args.m}x{args.n} tile {args.tile} mode {args.mode}: {us:.2f} us per launch, "
+          f"{gbs:.0f} GB/s of 4*M*N bytes ({100 * gbs / 8000:.1f} % of 8 TB/s)", flush=True)
 
 
 def cmd_copy(args):
@@ -237,6 +260,13 @@ def main(argv=None):
     k.add_argument("--launches", type=int, default=4)
     k.add_argument("--group-m", type=int, nargs="+", default=[1, 2, 4, 8, 16])
     k.set_defaults(fn=cmd_rank)
+    t = sub.add_parser("transpose")
+    t.add_argument("--m", type=int, default=16384)
+    t.add_argument("--n", type=int, default=16384)
+    t.add_argument("--tile", type=int, default=64, choices=[32, 64])
+    t.add_argument("--mode", default="xcd_groupm", choices=["rr", "xcd", "xcd_groupm", "groupm"])
+    t.add_argument("--launches", type=int, default=10)
+    t.set_defaults(fn=cmd_transpose)
     c = sub.add_parser("copy")
     c.add_argument("--mib", type=int, default=1024)
     c.add_argument("--launches", type=int, default=3)

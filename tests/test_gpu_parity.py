@@ -288,3 +288,36 @@ def test_persistent_full_size_cfg5_is_bit_identical(swz):
     assert np.array_equal(pers[0], base) and np.array_equal(pers[2], base)
     ii, jj = sample_indices(10000, 7000, 256, 256, seed=11, n=1024)
     assert_within_tolerance(base[ii, jj], gemm_ref.gemm_elems(a, b, ii, jj), "cfg5 persistent samples")
+
+
+# ---------------------------------------------------------------------------- transpose (bit-exact)
+
+@pytest.mark.parametrize("tile", [32, 64])
+@pytest.mark.parametrize("M,N", [(8, 8), (64, 64), (200, 328), (1000, 72), (2048, 1024), (4104, 520)])
+def test_transpose_is_bit_exact_in_every_mode(swz, tile, M, N):
+    from oracle import transpose_ref
+    x = si.matrix_bf16(600 + M, 0, M, N, "normal")
+    want = transpose_ref.transpose(x)
+    xd = to_dev(x)
+    for mode in range(4):
+        out = torch.full((N, M), float("nan"), dtype=torch.bfloat16, device="cuda")
+        swz.transpose(xd, out, tile=tile, mode=mode)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_bits(out), want), (tile, mode)
+    out = swz.transpose(xd, tile=tile, mode=2, num_xcd=3, group_m=7)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(out), want)
+
+
+def test_transpose_error_paths(swz):
+    x = to_dev(si.matrix_bf16(1, 0, 64, 64, "uniform"))
+    y = torch.full((64, 64), 2.0, dtype=torch.bfloat16, device="cuda")
+    L = swz.lib
+    s = torch.cuda.current_stream().cuda_stream
+    assert L.swz_transpose(x.data_ptr(), y.data_ptr(), 64, 64, 2, 48, 0, None, s) == -2     # tile
+    assert L.swz_transpose(x.data_ptr(), y.data_ptr(), 64, 64, 4, 64, 0, None, s) == -2     # element size
+    assert L.swz_transpose(x.data_ptr(), y.data_ptr(), 60, 64, 2, 64, 0, None, s) == -2     # M % 8
+    assert L.swz_transpose(x.data_ptr(), y.data_ptr(), 64, 64, 2, 64, 9, None, s) == -1     # mode
+    assert L.swz_transpose(None, y.data_ptr(), 64, 64, 2, 64, 0, None, s) == -1
+    torch.cuda.synchronize()
+    assert (y == 2.0).all()

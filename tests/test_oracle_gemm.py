@@ -101,3 +101,16 @@ def test_bf16_output_rounding_leaves_margin_under_the_tolerance():
     rounded = si.bf16_bits_to_f64(si.f32_to_bf16_bits(ref.astype(np.float32)))
     assert gemm_ref.within_tolerance(rounded, ref).all()
     assert (np.abs(rounded - ref) <= np.abs(ref) * 2.0 ** -8 + 1e-30).all()
+
+
+# ---------------------------------------------------------------------------- transpose oracle
+
+def test_transpose_oracle_pins():
+    from oracle import transpose_ref
+    assert transpose_ref.transpose_loops([[1, 2, 3], [4, 5, 6]]) == [[1, 4], [2, 5], [3, 6]]
+    x = si.matrix_bf16(3, 0, 24, 40, "uniform")
+    t = transpose_ref.transpose(x)
+    assert t.shape == (40, 24) and t.flags["C_CONTIGUOUS"]
+    assert t.tolist() == transpose_ref.transpose_loops(x.tolist())
+    assert np.array_equal(transpose_ref.transpose(t), x)                 # involution
+    assert t[7, 5] == x[5, 7] and t[39, 0] == x[0, 39]
