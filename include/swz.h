@@ -139,6 +139,33 @@ int swz_gemm_plan(int64_t M, int64_t N, int64_t K, const swz_params* params, swz
 int swz_transpose(const void* in, void* out, int64_t M, int64_t N, int elem_bytes, int tile, int mode,
                   const swz_params* params, hipStream_t stream);
 
+/* Row softmax, y[i][j] = exp(x[i][j] - max_i) / sum_k exp(x[i][k] - max_i), over a row-major dense
+ * M x N bfloat16 matrix (the paper's softmax kernel: Results; Appendix "Case Study: Other Swizzling
+ * Pattern Examples", whose swizzle routes all column chunks of a row to one XCD).  Each row is cut
+ * into `chunks` column chunks of ceil(N/8/chunks) 16-byte vectors (trailing chunks may be empty);
+ * one workgroup reads the whole row for the row statistics and writes one chunk.  The grid is
+ * M x chunks and hardware workgroup ids are decoded exactly as swz_pid_map does for that grid
+ * (tile row = matrix row, tile column = chunk; `mode`, params->group_m, params->num_xcd; other
+ * fields ignored).  chunks = 1 gives one workgroup per row, except that rows of at most 2048
+ * elements are then handled one per wave: the grid is ceil(M/4) x 1 groups of four consecutive rows.
+ *   in, out : caller-owned DEVICE pointers, 16-byte aligned, must not overlap.  -inf entries are
+ *             allowed (they get probability 0); a row of only -inf gives NaN.
+ *   fp32 arithmetic, one rounding to bfloat16 (nearest even); the result bits never depend on
+ *   `mode`, and for N > 2048 not on `chunks` either.
+ * Asynchronous on `stream`; never allocates or synchronises.
+ * Errors: INVALID_ARG (null, M/N/chunks < 1, chunks > N/8, unknown mode), UNSUPPORTED (N not a
+ * multiple of 8 or above 2^24, misaligned pointer), OVERFLOW (M*chunks or a dimension >= 2^31), HIP. */
+int swz_softmax(const void* in, void* out, int64_t M, int64_t N, int chunks, int mode, const swz_params* params,
+                hipStream_t stream);
+
+/* Layer normalisation of every row, y[i][j] = (x[i][j] - mean_i) / sqrt(var_i + eps) * gamma[j] + beta[j]
+ * with the biased variance (the paper's layer normalisation kernel, same appendix: all column chunks
+ * of a row on one XCD).  Same decomposition, grid, mapping, layout and error behaviour as swz_softmax.
+ *   gamma, beta : DEVICE pointers to N bfloat16 each, 16-byte aligned.   eps >= 0.
+ *   Mean and variance are accumulated in fp32 with pairwise (count, mean, M2) merges. */
+int swz_layernorm(const void* in, const void* gamma, const void* beta, void* out, int64_t M, int64_t N, float eps,
+                  int chunks, int mode, const swz_params* params, hipStream_t stream);
+
 /* Measurement aid, not part of the GEMM path: a plain streaming copy of `bytes` bytes
  * (reads `bytes`, writes `bytes`; both DEVICE pointers 16-byte aligned, bytes a multiple of
  * 16, buffers must not overlap).  The profiling harness scales the profiler's HBM byte

@@ -17,7 +17,8 @@ MODES = {"rr": MODE_RR, "xcd": MODE_XCD, "xcd_groupm": MODE_XCD_GROUPM, "groupm"
 DTYPE_BF16 = 0
 
 EXPORTS = ("swz_status_string", "swz_device_info", "swz_pid_map", "swz_pid_map_device", "swz_gemm", "swz_gemm_ex",
-           "swz_gemm_plan", "swz_copy_bytes", "swz_pid_map_persistent", "swz_pid_map_persistent_device", "swz_transpose")
+           "swz_gemm_plan", "swz_copy_bytes", "swz_pid_map_persistent", "swz_pid_map_persistent_device", "swz_transpose",
+           "swz_softmax", "swz_layernorm")
 
 
 class SwzParams(ctypes.Structure):
@@ -68,6 +69,8 @@ def _load() -> ctypes.CDLL:
     L.swz_gemm_plan.argtypes = [i64, i64, i64, pp, pp, ip, ip]
     L.swz_copy_bytes.argtypes = [vp, vp, i64, vp]
     L.swz_transpose.argtypes = [vp, vp, i64, i64, i, i, i, pp, vp]
+    L.swz_softmax.argtypes = [vp, vp, i64, i64, i, i, pp, vp]
+    L.swz_layernorm.argtypes = [vp, vp, vp, vp, i64, i64, ctypes.c_float, i, i, pp, vp]
     L.swz_pid_map_persistent.argtypes = [i, i, i, i, i, i, vp]
     L.swz_pid_map_persistent_device.argtypes = [i, i, i, i, i, i, vp, vp, vp]
     for name in EXPORTS:
@@ -204,4 +207,33 @@ def transpose(x, out=None, tile: int = 64, mode: int = MODE_XCD_GROUPM, stream=N
     p = _params(**params)
     _check(lib.swz_transpose(x.data_ptr(), out.data_ptr(), M, N, 2, int(tile), int(mode), ctypes.byref(p),
                              _stream_handle(stream)), "swz_transpose")
+    return out
+
+
+def _row_args(x, out):
+    import torch
+    assert x.is_cuda and x.is_contiguous() and x.dim() == 2 and x.dtype == torch.bfloat16
+    if out is None:
+        out = torch.empty_like(x)
+    assert out.is_cuda and out.is_contiguous() and out.shape == x.shape and out.dtype == x.dtype
+    return out
+
+
+def softmax(x, out=None, chunks: int = 1, mode: int = MODE_XCD, stream=None, **params):
+    """Row softmax of a bf16 matrix on the GPU through swz_softmax; `chunks` workgroups per row."""
+    out = _row_args(x, out)
+    p = _params(**params)
+    _check(lib.swz_softmax(x.data_ptr(), out.data_ptr(), x.shape[0], x.shape[1], int(chunks), int(mode), ctypes.byref(p),
+                           _stream_handle(stream)), "swz_softmax")
+    return out
+
+
+def layernorm(x, gamma, beta, out=None, eps: float = 1e-5, chunks: int = 1, mode: int = MODE_XCD, stream=None, **params):
+    """Layer normalisation of every row of a bf16 matrix on the GPU through swz_layernorm."""
+    out = _row_args(x, out)
+    for t in (gamma, beta):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == x.dtype and t.numel() == x.shape[1]
+    p = _params(**params)
+    _check(lib.swz_layernorm(x.data_ptr(), gamma.data_ptr(), beta.data_ptr(), out.data_ptr(), x.shape[0], x.shape[1],
+                             float(eps), int(chunks), int(mode), ctypes.byref(p), _stream_handle(stream)), "swz_layernorm")
     return out

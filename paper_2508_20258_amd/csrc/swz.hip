@@ -8,6 +8,7 @@
 #include "../../include/swz.h"
 #include "gemm_kernel.h"
 #include "pid_decode.h"
+#include "rowwise_kernel.h"
 #include "transpose_kernel.h"
 
 namespace {
@@ -138,6 +139,60 @@ int launch_transpose(const void* in, void* out, int M, int N, int gm, int gn, in
   }
   return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
 }
+// How the two row-wise entry points launch: threads per row (256, or 64 = one row per wave when a
+// single workgroup per row is asked for and the row has at most 2048 elements), 16-byte vectors a
+// thread keeps in registers (0 = the row is streamed twice), the grid and the mapping parameters.
+struct RowPlan {
+  int tpr, keep, grid_m, chunk_vecs, num_xcd, group_m;
+};
+
+int resolve_rows(int64_t M, int64_t N, int chunks, int mode, const swz_params* params, RowPlan* plan) {
+  if (M < 1 || N < 1 || chunks < 1 || !valid_mode(mode)) return SWZ_ERR_INVALID_ARG;
+  const int64_t lim = (int64_t)1 << 31;
+  if (M >= lim || N >= lim || M * chunks >= lim) return SWZ_ERR_OVERFLOW;
+  if ((N % 8) != 0 || N > ((int64_t)1 << 24)) return SWZ_ERR_UNSUPPORTED;   // 16-byte vectors; fp32 element counts stay exact
+  const int64_t nv = N / 8;
+  if (chunks > nv) return SWZ_ERR_INVALID_ARG;
+  plan->group_m = 4;
+  plan->num_xcd = 0;
+  if (params != nullptr) {
+    if (params->group_m < 0 || params->num_xcd < 0) return SWZ_ERR_INVALID_ARG;
+    if (params->group_m > 0) plan->group_m = params->group_m;
+    plan->num_xcd = params->num_xcd;
+  }
+  if (plan->num_xcd == 0) {
+    DeviceFacts f;
+    const int st = query_device(&f);
+    if (st != SWZ_OK) return st;
+    plan->num_xcd = f.num_xcd;
+  }
+  plan->chunk_vecs = (int)((nv + chunks - 1) / chunks);
+  plan->tpr = (chunks == 1 && nv <= 4 * 64) ? 64 : swz::kRowThreads;
+  const int64_t per_thread = (nv + plan->tpr - 1) / plan->tpr;
+  plan->keep = chunks != 1 ? 0 : per_thread <= 4 ? 4 : per_thread <= 16 ? 16 : 0;
+  const int rows_per_wg = swz::kRowThreads / plan->tpr;
+  plan->grid_m = (int)((M + rows_per_wg - 1) / rows_per_wg);
+  return check_map_args(plan->grid_m, chunks, plan->num_xcd, &plan->group_m, mode);
+}
+
+#define SWZ_LAUNCH_BY_MODE(KERNEL, KEEP, TPR, ...)                                                                       \
+  switch (mode) {                                                                                                        \
+    case SWZ_MODE_RR: hipLaunchKernelGGL((KERNEL<kModeRR, KEEP, TPR>), grid, block, 0, stream, __VA_ARGS__); break;       \
+    case SWZ_MODE_XCD: hipLaunchKernelGGL((KERNEL<kModeXcd, KEEP, TPR>), grid, block, 0, stream, __VA_ARGS__); break;     \
+    case SWZ_MODE_XCD_GROUPM: hipLaunchKernelGGL((KERNEL<kModeXcdGroupM, KEEP, TPR>), grid, block, 0, stream, __VA_ARGS__); break; \
+    case SWZ_MODE_GROUPM: hipLaunchKernelGGL((KERNEL<kModeGroupM, KEEP, TPR>), grid, block, 0, stream, __VA_ARGS__); break; \
+    default: return SWZ_ERR_INVALID_ARG;                                                                                 \
+  }
+#define SWZ_LAUNCH_BY_PLAN(KERNEL, ...)                                          \
+  if (plan.tpr == 64) {                                                          \
+    SWZ_LAUNCH_BY_MODE(KERNEL, 4, 64, __VA_ARGS__)                               \
+  } else if (plan.keep == 4) {                                                   \
+    SWZ_LAUNCH_BY_MODE(KERNEL, 4, 256, __VA_ARGS__)                              \
+  } else if (plan.keep == 16) {                                                  \
+    SWZ_LAUNCH_BY_MODE(KERNEL, 16, 256, __VA_ARGS__)                             \
+  } else {                                                                       \
+    SWZ_LAUNCH_BY_MODE(KERNEL, 0, 256, __VA_ARGS__)                              \
+  }
 }  // namespace
 
 extern "C" {
@@ -246,6 +301,35 @@ int swz_transpose(const void* in, void* out, int64_t M, int64_t N, int elem_byte
   if (st != SWZ_OK) return st;
   return tile == 64 ? launch_transpose<64>(in, out, (int)M, (int)N, (int)gm, (int)gn, num_xcd, group_m, mode, stream)
                     : launch_transpose<32>(in, out, (int)M, (int)N, (int)gm, (int)gn, num_xcd, group_m, mode, stream);
+}
+
+int swz_softmax(const void* in, void* out, int64_t M, int64_t N, int chunks, int mode, const swz_params* params,
+                hipStream_t stream) {
+  if (in == nullptr || out == nullptr) return SWZ_ERR_INVALID_ARG;
+  RowPlan plan;
+  const int st = resolve_rows(M, N, chunks, mode, params, &plan);
+  if (st != SWZ_OK) return st;
+  if ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) return SWZ_ERR_UNSUPPORTED;
+  const dim3 grid((unsigned)((int64_t)plan.grid_m * chunks)), block(swz::kRowThreads);
+  SWZ_LAUNCH_BY_PLAN(swz::softmax_rows_kernel, static_cast<const uint16_t*>(in), static_cast<uint16_t*>(out), (int)M,
+                     (int)N, chunks, plan.chunk_vecs, plan.num_xcd, plan.group_m)
+  return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
+}
+
+int swz_layernorm(const void* in, const void* gamma, const void* beta, void* out, int64_t M, int64_t N, float eps,
+                  int chunks, int mode, const swz_params* params, hipStream_t stream) {
+  if (in == nullptr || gamma == nullptr || beta == nullptr || out == nullptr || !(eps >= 0.f)) return SWZ_ERR_INVALID_ARG;
+  RowPlan plan;
+  const int st = resolve_rows(M, N, chunks, mode, params, &plan);
+  if (st != SWZ_OK) return st;
+  if ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(gamma) |
+       reinterpret_cast<uintptr_t>(beta)) & 15)
+    return SWZ_ERR_UNSUPPORTED;
+  const dim3 grid((unsigned)((int64_t)plan.grid_m * chunks)), block(swz::kRowThreads);
+  SWZ_LAUNCH_BY_PLAN(swz::layernorm_rows_kernel, static_cast<const uint16_t*>(in), static_cast<const uint16_t*>(gamma),
+                     static_cast<const uint16_t*>(beta), static_cast<uint16_t*>(out), (int)M, (int)N, eps, chunks,
+                     plan.chunk_vecs, plan.num_xcd, plan.group_m)
+  return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
 }
 
 int swz_copy_bytes(const void* src, void* dst, int64_t bytes, hipStream_t stream) {

@@ -4,6 +4,7 @@ reader that turns rocprofv3's CSV output into the summaries kept with the measur
     python -m paper_2508_20258_amd.harness run --workload cfg2_4096 --mode xcd_groupm --launches 10
     python -m paper_2508_20258_amd.harness copy --mib 1024 --launches 3
     python -m paper_2508_20258_amd.harness transpose --m 16384 --n 16384 --tile 32 --mode rr
+    python -m paper_2508_20258_amd.harness rows --op softmax --m 8192 --n 8192 --chunks 8 --mode xcd
     python -m paper_2508_20258_amd.harness summarize <rocprofv3 output dir>
     python -m paper_2508_20258_amd.harness rank --workload cfg4_skinny
 
@@ -133,6 +134,37 @@ def cmd_transpose(args):
     us = e0.elapsed_time(e1) * 1e3 / max(args.launches - 1, 1)
     gbs = 4.0 * args.m * args.n / (us * 1e-6) / 1e9
     print(f"ran {args.launches} transposes {args.m}x{args.n} tile {args.tile} mode {args.mode}: {us:.2f} us per launch, "
+          f"{gbs:.0f} GB/s of 4*M*N bytes ({100 * gbs / 8000:.1f} % of 8 TB/s)", flush=True)
+
+
+def cmd_rows(args):
+    import torch
+
+    import paper_2508_20258_amd as swz
+    torch.manual_seed(0)
+    x = (torch.randn((args.m, args.n), device="cuda") * 2.0).to(torch.bfloat16)
+    out = torch.empty_like(x)
+    g = torch.rand(args.n, device="cuda").to(torch.bfloat16)
+    b = torch.rand(args.n, device="cuda").to(torch.bfloat16)
+    mode = swz.MODES[args.mode]
+
+    def launch():
+        if args.op == "softmax":
+            swz.softmax(x, out, chunks=args.chunks, mode=mode)
+        else:
+            swz.layernorm(x, g, b, out, eps=1e-5, chunks=args.chunks, mode=mode)
+
+    launch()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(max(args.launches - 1, 1)):
+        launch()
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / max(args.launches - 1, 1)
+    gbs = 4.0 * args.m * args.n / (us * 1e-6) / 1e9
+    print(f"ran {args.launches} x {args.op} {args.m}x{args.n} chunks {args.chunks} mode {args.mode}: {us:.2f} us per launch, "
           f"{gbs:.0f} GB/s of 4*M*N bytes ({100 * gbs / 8000:.1f} % of 8 TB/s)", flush=True)
 
 
@@ -267,6 +299,14 @@ def main(argv=None):
     t.add_argument("--mode", default="xcd_groupm", choices=["rr", "xcd", "xcd_groupm", "groupm"])
     t.add_argument("--launches", type=int, default=10)
     t.set_defaults(fn=cmd_transpose)
+    w = sub.add_parser("rows")
+    w.add_argument("--op", default="softmax", choices=["softmax", "layernorm"])
+    w.add_argument("--m", type=int, default=8192)
+    w.add_argument("--n", type=int, default=8192)
+    w.add_argument("--chunks", type=int, default=8)
+    w.add_argument("--mode", default="xcd", choices=["rr", "xcd", "xcd_groupm", "groupm"])
+    w.add_argument("--launches", type=int, default=10)
+    w.set_defaults(fn=cmd_rows)
     c = sub.add_parser("copy")
     c.add_argument("--mib", type=int, default=1024)
     c.add_argument("--launches", type=int, default=3)
