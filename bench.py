@@ -5,7 +5,8 @@ decode, global->LDS staging, MFMA loop, epilogue) over the 4096^3 workload, inpu
 in HBM.  Prints ONE JSON line.  `value` is the throughput of the swizzled mapping (XCD
 renumbering + grouped-M raster) over exactly --steps timed launches; the round-robin and
 XCD-only mappings and the persistent launch style, timed interleaved in the same run, are
-reported beside it, as are the 8192^3 and the skinny 16384x2048x8192 workloads.
+reported beside it, as are the 8192^3 and the skinny 16384x2048x8192 workloads and, under
+"other_kernels", the transpose / softmax / layer normalisation kernels (HBM-bound; not part of `value`).
 """
 from __future__ import annotations
 
@@ -78,6 +79,51 @@ def compare_mappings(swz, torch, a, b, c, variants, per_pass, warmup, flops, pas
         t = flops / ms / 1e9
         out[name] = dict(ms=ms, tflops=t, pct_mfma_peak=100.0 * t / PEAK_BF16_TFLOPS)
     return out
+
+
+def time_calls(torch, fn, n=20):
+    """Average duration in us of n back-to-back calls of fn() on the current stream (after two warm-up calls)."""
+    for _ in range(2):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(n):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / n
+
+
+def other_kernels(swz, torch):
+    """The paper's other kernels built here (transpose, row softmax, layer normalisation): round-robin against the
+    remapped program ids, GB/s of the algorithmic 4*M*N bytes against the 8 TB/s HBM roofline."""
+    res = {}
+
+    def entry(us, m, n):
+        gbs = 4.0 * m * n / (us * 1e-6) / 1e9
+        return dict(us=us, gb_per_s=gbs, frac_hbm_peak=gbs / 8000.0)
+
+    m = n = 16384
+    x = torch.randint(-32768, 32767, (m, n), dtype=torch.int16, device="cuda").view(torch.bfloat16)
+    y = torch.empty((n, m), dtype=torch.bfloat16, device="cuda")
+    for tile in (64, 32):
+        for mode in ("rr", "xcd_groupm"):
+            us = time_calls(torch, lambda: swz.transpose(x, y, tile=tile, mode=swz.MODES[mode]))
+            res[f"transpose_{m}x{n}_tile{tile}_{mode}"] = entry(us, m, n)
+    del x, y
+    for (m, n, chunks) in ((1024, 65536, 8), (8192, 8192, 1)):
+        x = (torch.randn((m, n), device="cuda") * 2.0).to(torch.bfloat16)
+        y = torch.empty_like(x)
+        g = torch.rand(n, device="cuda").to(torch.bfloat16)
+        b = torch.rand(n, device="cuda").to(torch.bfloat16)
+        for mode in ("rr", "xcd"):
+            us = time_calls(torch, lambda: swz.softmax(x, y, chunks=chunks, mode=swz.MODES[mode]))
+            res[f"softmax_{m}x{n}_chunks{chunks}_{mode}"] = entry(us, m, n)
+            us = time_calls(torch, lambda: swz.layernorm(x, g, b, y, eps=1e-5, chunks=chunks, mode=swz.MODES[mode]))
+            res[f"layernorm_{m}x{n}_chunks{chunks}_{mode}"] = entry(us, m, n)
+        del x, y
+    return res
 
 
 def to_device(torch, np, bits):
@@ -184,6 +230,9 @@ def main():
             f3 = 2.0 * oc["M"] * oc["N"] * oc["K"]
             out["other_workloads"][other] = compare_mappings(swz, torch, a3, b3, c3, variants, 8, 4, f3)
             del a3, b3, c3, ab, bb
+
+    if not args.no_extras:
+        out["other_kernels"] = other_kernels(swz, torch)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(a_bits, b_bits, args.cpu_rows or M)
