@@ -15,7 +15,7 @@
 //   B ring: 4 slots, each 32 x BN (rows of B are whole lines already).
 // A CU's vector memory path moves 64 bytes per clock, so a 256x256x64 panel pair (64 KB) needs
 // >= 1024 clocks of transfer on top of the L2/HBM latency against 2048 clocks of MFMA work: the
-// loads run two to three steps ahead of their use.  A lane cannot choose where its bytes land,
+// loads run about three steps ahead of their use.  A lane cannot choose where its bytes land,
 // only what it fetches, so the XOR swizzle of the LDS layout is applied on the global-address
 // side: the lane that owns slot p of a row fetches chunk p ^ key(row).
 // Rows >= M and columns >= N are fetched from clamped, valid addresses (what they bring in only
@@ -36,12 +36,24 @@
 // flops: with random operands held in registers and no memory traffic the chip sustains
 // about 2.1 PFLOP/s with it against 1.9 PFLOP/s with 32x32x16 (the clock settles higher).
 //
-// Main loop.  While the MFMAs of K step t run, the LDS reads of step t+1 and a fixed share of
-// global loads are issued, one memory instruction per MFMA slot.  One workgroup barrier per
-// step, with no LDS-counter wait attached: a slot is refilled only after the barrier that
-// follows the step which consumed it.  Steps past the end of K are fetched as zeros, which
-// keeps the loop free of tail cases: every step issues the same number of loads and waits until
-// only its predecessor's are outstanding.
+// Main loop.  The eight waves form two groups of four; the two waves that share a SIMD are in
+// different groups.  Time is cut into phases separated by workgroup barriers.  In a phase one
+// group issues the 32 MFMAs of a K step back to back and nothing else, while the other group
+// does the memory work of its next step (its share of the global->LDS loads, then all fragment
+// reads from LDS) and waits for it; then the groups swap.  On each SIMD the MFMA pipe so sees
+// one uninterrupted instruction stream at a time.  Measured on the same device against a loop
+// in which every wave interleaves its own LDS reads and loads with its MFMAs: 1045-1070 clocks
+// per K step instead of 1240 (1024 = MFMA pipe never idle).  The reasons, each measured:
+//   * the SIMD issues MFMAs of the older wave first, so two waves that both have MFMAs ready do
+//     not alternate; one starves and its memory instructions, queued behind its MFMAs (issue is
+//     in order), come late;
+//   * an LDS read in the middle of a wave's MFMA stream costs that stream about 13 clocks;
+//   * in a memory phase nothing may be computed on the vector ALU per read: the 16 reads are one
+//     of eight precomputed address registers plus an immediate, which needs the position of the
+//     step in the ring cycle (12 steps: 4 B slots, 3 A doubles) at compile time, hence a main
+//     loop body of 12 steps.  With address arithmetic in the phase it took longer than the 512
+//     clocks of the other group's MFMAs and the MFMA pipe idled 10 % of the time.
+// Steps past the end of K are fetched as zeros, which keeps the loop free of tail cases.
 //
 // Epilogue.  Each wave converts its accumulators to bf16 (nearest even), writes them to a
 // wave-private LDS patch and reads them back row-wise, so that global stores are 16 bytes
@@ -58,6 +70,9 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
+#include <utility>
 
 #include <type_traits>
 
@@ -124,6 +139,13 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const unsigned char* p) {
 // the memory clobber keeps the compiler from moving LDS accesses across it.
 __device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
+// s_waitcnt on the vector-memory counter (<= VM) and the LDS counter (<= LGKM) together.
+template <int VM, int LGKM>
+__device__ __forceinline__ void wait_vmcnt_lgkmcnt() {
+  static_assert(VM >= 0 && VM < 64 && LGKM >= 0 && LGKM < 16, "counter ranges");
+  __builtin_amdgcn_s_waitcnt((VM & 0xF) | 0x0070 | (LGKM << 8) | ((VM >> 4) << 14));
+}
+
 // s_waitcnt that waits only for the vector-memory counter to drop to n.
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -148,6 +170,12 @@ __device__ __forceinline__ void load_to_lds_base_off(const void* base, uint32_t 
 // One BM x BN tile of C, tile row pm, tile column pn, by the whole workgroup.  On return every
 // wave has issued its stores; LDS may still be read by slower waves (callers that reuse it put a
 // barrier first).
+// f(integral_constant<int, 0>{}), f(integral_constant<int, 1>{}), ... in order.
+template <class F, int... Is>
+__device__ __forceinline__ void for_each_index(F&& f, std::integer_sequence<int, Is...>) {
+  (f(std::integral_constant<int, Is>{}), ...);
+}
+
 template <class S>
 __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
                                           uint16_t* __restrict__ C, int M, int N, int K, int pm, int pn,
@@ -167,14 +195,12 @@ __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const 
   // 8 rows x 128 bytes.  B load i fills [(w*B_LOADS + i)*1024, +1024) of a B slot: 2 rows x 512 bytes.
   // A lane's source is  tile base (uniform, advances with k) + a 32-bit byte offset that never changes.
   uint32_t a_off[S::A_LOADS], b_off[S::B_LOADS];
-  int a_k[S::A_LOADS], b_k[S::B_LOADS];       // k offset of the chunk inside its double / step
 #pragma unroll
   for (int i = 0; i < S::A_LOADS; ++i) {
     const int q = (wave * S::A_LOADS + i) * 64 + lane;
     const int row = q >> 3, slot = q & 7;
     const int c = a_slot(row, slot);           // XOR with a key is its own inverse
     const int r = (m0 + row < M) ? row : (M - 1 - m0);
-    a_k[i] = c * 8;
     a_off[i] = (uint32_t)r * (uint32_t)K * 2u + (uint32_t)c * 16u;
   }
 #pragma unroll
@@ -183,7 +209,6 @@ __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const 
     const int krow = q / S::B_ROW_CHUNKS, slot = q % S::B_ROW_CHUNKS;
     const int c = slot ^ b_key(krow);
     const int col = (n0 + c * 8 < N) ? c * 8 : (N - 8 - n0);
-    b_k[i] = krow;
     b_off[i] = (uint32_t)krow * (uint32_t)N * 2u + (uint32_t)col * 2u;
   }
   const unsigned char* a_tile = reinterpret_cast<const unsigned char*>(A + (size_t)m0 * K);
@@ -194,23 +219,26 @@ __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const 
   const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;   // LDS byte address of the rings
 
   // Load i of A double d into its ring slot.  full = the double lies wholly inside K (uniform).
-  auto load_a = [&](int d, int i, auto full) __attribute__((always_inline)) {
+  auto load_a = [&](int d, int slot, int i, auto full) __attribute__((always_inline)) {
     const unsigned char* base = a_tile + d * a_dbl;
-    const uint32_t dst = smem_addr + (d % kASlots) * S::A_SLOT_BYTES + (wave * S::A_LOADS + i) * 1024;
+    const uint32_t dst = smem_addr + slot * S::A_SLOT_BYTES + (wave * S::A_LOADS + i) * 1024;
     if constexpr (decltype(full)::value) {
       load_to_lds_base_off(base, a_off[i], dst);
     } else {
-      load_to_lds(d * 2 * kStepK + a_k[i] < K ? base + a_off[i] : zero, dst);
+      const int q = (wave * S::A_LOADS + i) * 64 + lane;          // which chunk this is: only this (tail) path needs it
+      const int ak = a_slot(q >> 3, q & 7) * 8;
+      load_to_lds(d * 2 * kStepK + ak < K ? base + a_off[i] : zero, dst);
     }
   };
   // Load i of B step t into its ring slot.
-  auto load_b = [&](int t, int i, auto full) __attribute__((always_inline)) {
+  auto load_b = [&](int t, int slot, int i, auto full) __attribute__((always_inline)) {
     const unsigned char* base = b_tile + t * b_step;
-    const uint32_t dst = smem_addr + S::A_RING_BYTES + (t % kBSlots) * S::B_SLOT_BYTES + (wave * S::B_LOADS + i) * 1024;
+    const uint32_t dst = smem_addr + S::A_RING_BYTES + slot * S::B_SLOT_BYTES + (wave * S::B_LOADS + i) * 1024;
     if constexpr (decltype(full)::value) {
       load_to_lds_base_off(base, b_off[i], dst);
     } else {
-      load_to_lds(t * kStepK + b_k[i] < K ? base + b_off[i] : zero, dst);
+      const int bk = ((wave * S::B_LOADS + i) * 64 + lane) / S::B_ROW_CHUNKS;
+      load_to_lds(t * kStepK + bk < K ? base + b_off[i] : zero, dst);
     }
   };
   constexpr std::true_type kFull{};
@@ -230,111 +258,148 @@ __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const 
   const int b_krow0 = 8 * (lane >> 4) + ((lane & 15) >> 2); // (+4 for the upper half)
   const int b_col0 = wn * (TN * 16) + 4 * (lane & 3);       // + 16*bj
 
-  // Fragment registers.  The MFMAs of a step run A-row-block by A-row-block (bi outer, bj
-  // inner), so an A fragment is dead after its TN MFMAs and the same registers take the next
-  // step's fragment right away; B fragments are needed by every row-block and are double
-  // buffered.  A B fragment is two 8-byte halves.
+  // Fragment registers: one set per wave (a wave reads the fragments of a step, then issues that
+  // step's MFMAs; nothing of the next step is touched in between).  A B fragment is two 8-byte halves.
   bf16x8 af[TM];
-  s16x4 bq[2][TN][2];
+  s16x4 bq[TN][2];
   constexpr int NM = TM * TN;             // MFMAs per step
-  // A fragment bi of K step t (t = 2*double + half).
-  auto read_a = [&](int a_slot_idx, int half, int bi) __attribute__((always_inline)) {
-    const unsigned char* sA = smem + a_slot_idx * S::A_SLOT_BYTES;
-    af[bi] = *reinterpret_cast<const bf16x8*>(sA + a_lds_off(a_row0 + 16 * bi, a_kc0 + 4 * half));
+  // LDS byte addresses of this lane's part of the fragments, ring slot 0: computed once and
+  // hidden from the optimiser, so that every read is "one of these registers + a constant" and
+  // the constant (slot, row block, k half) goes into the instruction's 16-bit offset field.
+  // A slots further than that field reaches get a second base, kAFar bytes up.
+  typedef __attribute__((address_space(3))) const bf16x8* lds_a_ptr;
+  typedef __attribute__((address_space(3))) s16x4* lds_b_ptr;
+  constexpr uint32_t kAFar = 65536;
+  auto opaque = [](uint32_t x) __attribute__((always_inline)) {
+    asm volatile("" : "+v"(x));
+    return x;
   };
-  auto read_b = [&](int buf, int b_slot_idx, int bj, int hi) __attribute__((always_inline)) {
-    const unsigned char* sB = smem + S::A_RING_BYTES + b_slot_idx * S::B_SLOT_BYTES;
+  uint32_t a_rd[2][2], b_rd[TN];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    a_rd[h][0] = opaque(smem_addr + (uint32_t)a_lds_off(a_row0, a_kc0 + 4 * h));
+    a_rd[h][1] = opaque(a_rd[h][0] + kAFar);
+  }
+#pragma unroll
+  for (int bj = 0; bj < TN; ++bj) {
     const int col = b_col0 + 16 * bj;
-    const int kr = b_krow0 + 4 * hi;
-    bq[buf][bj][hi] = lds_read_tr16(sB + b_lds_off<BN>(kr, col >> 3) + (col & 7) * 2);
+    b_rd[bj] = opaque(smem_addr + (uint32_t)(S::A_RING_BYTES + b_lds_off<BN>(b_krow0, col >> 3) + (col & 7) * 2));
+  }
+  // A fragment bi of K step t (t = 2*double + half): row block bi is 16 rows = 2048 bytes further
+  // (the swizzle key repeats every 16 rows).
+  auto read_a = [&](int a_slot_idx, int half, int bi) __attribute__((always_inline)) {
+    const uint32_t off = (uint32_t)a_slot_idx * S::A_SLOT_BYTES + (uint32_t)bi * 2048u;
+    const bool far = __builtin_constant_p(off) && off >= kAFar;
+    af[bi] = far ? *(lds_a_ptr)(uintptr_t)(a_rd[half][1] + (off - kAFar)) : *(lds_a_ptr)(uintptr_t)(a_rd[half][0] + off);
   };
-  auto mfma = [&](int buf, int bi, int bj) __attribute__((always_inline)) {
-    const bf16x8 b = __builtin_bit_cast(bf16x8, __builtin_shufflevector(bq[buf][bj][0], bq[buf][bj][1], 0, 1, 2, 3, 4, 5, 6, 7));
+  // B fragment bj, half hi: rows 4 further down = 4*BN*2 bytes (the key depends on k mod 4 and on
+  // bit 3 of k only, and the lane's first row has k mod 8 < 4).
+  auto read_b = [&](int b_slot_idx, int bj, int hi) __attribute__((always_inline)) {
+    const uint32_t off = (uint32_t)b_slot_idx * S::B_SLOT_BYTES + (uint32_t)hi * (4u * BN * 2u);
+    bq[bj][hi] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_b_ptr)(uintptr_t)(b_rd[bj] + off));
+  };
+  auto mfma = [&](int bi, int bj) __attribute__((always_inline)) {
+    const bf16x8 b = __builtin_bit_cast(bf16x8, __builtin_shufflevector(bq[bj][0], bq[bj][1], 0, 1, 2, 3, 4, 5, 6, 7));
     acc[bi][bj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b, af[bi], acc[bi][bj], 0, 0, 0);
   };
 
-  // One K step, issued as NM slots.  Slot i = MFMA (bi, bj) on the fragments of the current
-  // step, then at most one LDS read for the next step (the B halves in the first 2*TN slots,
-  // the A fragment of row-block bi after that block's last MFMA), then, in the middle of every
-  // (NM/LOADS)-th run of slots, one global->LDS load.  Nothing moves across slot boundaries, so
-  // memory instructions are fed to their queues at the pace of the MFMA pipe instead of in
-  // bursts that would block the (in-order) wave.
-  //   HALF   = t & 1 (compile time): fragment buffer of this step's B, and which half of the
-  //            A double the NEXT step reads (1 - HALF).
-  //   loads  : A loads [HALF*A_LOADS/2, +A_LOADS/2) of double ld_d, B loads of step ld_t.
-  constexpr int SEG = NM / S::LOADS;
-  static_assert(NM % S::LOADS == 0 && 2 * TN <= NM, "slot schedule");
-  auto kblock = [&](auto half_tag, int rd_a_slot, int rd_b_slot, int ld_d, int ld_t, auto full) __attribute__((always_inline)) {
+  // The eight waves form two groups of four (group = wave / 4; the two waves that share a SIMD
+  // are in different groups).  Time is cut into phases; in every phase one group issues the 32
+  // MFMAs of a K step back to back while the other group does the memory work of its next step
+  // (fragment reads from LDS, its share of global->LDS loads), then the groups swap.  A barrier
+  // separates the phases, so on each SIMD the MFMA pipe sees one uninterrupted stream and the
+  // memory instructions of the other wave never queue behind an MFMA.
+  //   group 0:  MEM(0) | CMP(0) | MEM(1) | CMP(1) | ...
+  //   group 1:    -    | MEM(0) | CMP(0) | MEM(1) | ...
+  // MEM(u) reads the fragments of step u (A double u/2, half u&1; B slot u%4) and issues half the
+  // loads of A double u/2 + 2 and the loads of B step u + 3.
+  //   * data: step u's data was issued by MEM(u-3) at the latest; every wave ends MEM(v) by waiting
+  //     until only the loads of MEM(v) and MEM(v-1) are outstanding, so before the barrier that
+  //     precedes group 0's MEM(u) everybody has waited for MEM(u-3)'s loads (group 0 at the end of
+  //     MEM(u-1), group 1 at the end of MEM(u-1) too, one phase later but before the same barrier).
+  //   * slots: MEM(u) refills B slot (u-1)%4 and, for even u, starts on the A slot of double
+  //     u/2 - 1; their last readers were group 1's MEM(u-1), which ended with an LDS-counter wait
+  //     before the barrier that precedes group 0's MEM(u).
+  static_assert(S::NW == 8, "two groups of four waves");
+  const int grp = wave >> 2;
+  // rd_as / rd_bs: ring slots MEM(u) reads; ld_as / ld_bs: ring slots its loads fill
+  auto mem_phase = [&](auto half_tag, int u, int rd_as, int rd_bs, int ld_as, int ld_bs, auto full) __attribute__((always_inline)) {
     constexpr int HALF = decltype(half_tag)::value;
+    const int d = u >> 1;
 #pragma unroll
-    for (int i = 0; i < NM; ++i) {
-      const int bi = i / TN, bj = i % TN;
-      mfma(HALF, bi, bj);
-      if (i < 2 * TN) read_b(HALF ^ 1, rd_b_slot, i / 2, i % 2);
-      if (bj == TN - 1) read_a(rd_a_slot, HALF ^ 1, bi);
-      if (i % SEG == SEG / 2) {
-        const int l = i / SEG;                       // 0 .. LOADS-1: A, B, A, B, ...
-        if ((l & 1) == 0) load_a(ld_d, HALF * (S::A_LOADS / 2) + (l >> 1), full);
-        else load_b(ld_t, l >> 1, full);
-      }
-      __builtin_amdgcn_sched_barrier(0);
+    for (int i = 0; i < S::A_LOADS / 2; ++i) load_a(d + 2, ld_as, HALF * (S::A_LOADS / 2) + i, full);
+#pragma unroll
+    for (int i = 0; i < S::B_LOADS; ++i) load_b(u + 3, ld_bs, i, full);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int bj = 0; bj < TN; ++bj) {
+      read_b(rd_bs, bj, 0);
+      read_b(rd_bs, bj, 1);
     }
+#pragma unroll
+    for (int bi = 0; bi < TM; ++bi) read_a(rd_as, HALF, bi);
+    wait_vmcnt_lgkmcnt<2 * S::LOADS, 0>();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto compute_phase = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < NM; ++i) mfma(i / TN, i % TN);
+    __builtin_amdgcn_sched_barrier(0);
+    block_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto phase_barrier = [&]() __attribute__((always_inline)) {
+    block_barrier();
+    __builtin_amdgcn_sched_barrier(0);
   };
 
-  // Step t reads A from double t/2 (half t&1) and B from B slot t%4.  During step t a wave issues
-  // the MFMAs of step t, the LDS reads of step t+1, and its share of loads: half of A double
-  // t/2 + 2 (into the slot of double t/2 - 1) and B step t+3 (into the slot of step t-1).
-  //   * the reads of step t+1 need its data landed for everybody: each wave waits until only the
-  //     loads of the step before are outstanding (everything older has landed, which covers B step
-  //     t+1 and A double (t+1)/2, both issued by step t-2 at the latest) and then meets the others
-  //     at the barrier that opens step t;
-  //   * the refills overwrite slots whose last reader was step t-1: every wave consumed those
-  //     fragments in the MFMAs it issued before arriving at the same barrier, so the reads have
-  //     completed and the barrier needs no wait on the LDS counter.
-  // Two steps per loop trip keep the half index a compile-time constant; an odd step count just
-  // processes one more step of zeros.
   const int KT = (K + kStepK - 1) / kStepK;
-  // prologue: A doubles 0 and 1, B steps 0 .. 2 (what steps 0 and 1 do not fetch themselves), in an
-  // order that leaves as the most recent LOADS loads only things step 0 does not read (the second
-  // half of A double 1 and B step 2): the wait at the barrier of step 0 then covers B step 1.
+  // prologue: A doubles 0 and 1, B steps 0 .. 2 (what MEM(0) and MEM(1) do not fetch themselves)
   static_assert(kBSlots == 4 && kASlots == 3, "prologue order is written for these ring depths");
 #pragma unroll
-  for (int i = 0; i < S::A_LOADS; ++i) load_a(0, i, kTail);
+  for (int i = 0; i < S::A_LOADS; ++i) load_a(0, 0, i, kTail);
 #pragma unroll
-  for (int i = 0; i < S::B_LOADS; ++i) load_b(0, i, kTail);
+  for (int i = 0; i < S::B_LOADS; ++i) load_b(0, 0, i, kTail);
 #pragma unroll
-  for (int i = 0; i < S::B_LOADS; ++i) load_b(1, i, kTail);
+  for (int i = 0; i < S::B_LOADS; ++i) load_b(1, 1, i, kTail);
 #pragma unroll
-  for (int i = 0; i < S::A_LOADS; ++i) load_a(1, i, kTail);
+  for (int i = 0; i < S::A_LOADS; ++i) load_a(1, 1, i, kTail);
 #pragma unroll
-  for (int i = 0; i < S::B_LOADS; ++i) load_b(2, i, kTail);
+  for (int i = 0; i < S::B_LOADS; ++i) load_b(2, 2, i, kTail);
   wait_vmcnt<S::A_LOADS + (kBSlots - 2) * S::B_LOADS>();          // A double 0 and B step 0 have landed (this wave's part)
   __syncthreads();                                               // ... and everybody else's
-#pragma unroll
-  for (int bj = 0; bj < TN; ++bj) {
-    read_b(0, 0, bj, 0);
-    read_b(0, 0, bj, 1);
-  }
-#pragma unroll
-  for (int bi = 0; bi < TM; ++bi) read_a(0, 0, bi);
+  if (grp == 1) phase_barrier();                                 // group 1 starts one phase later
 
-  auto step_pair = [&](int t, auto full) __attribute__((always_inline)) {   // t even
-    const int d = t >> 1;
-    // step t: next step (t+1) reads the upper half of the same double
-    wait_vmcnt<S::LOADS>();
-    block_barrier();
-    kblock(std::integral_constant<int, 0>{}, d % kASlots, (t + 1) % kBSlots, d + 2, t + 3, full);
-    // step t+1: next step (t+2) reads the lower half of the next double
-    wait_vmcnt<S::LOADS>();
-    block_barrier();
-    kblock(std::integral_constant<int, 1>{}, (d + 1) % kASlots, (t + 2) % kBSlots, d + 2, t + 4, full);
+  // one step whose position in the slot cycle (B: 4 steps, A: 3 doubles = 6 steps, together 12)
+  // is a compile-time constant, so that every LDS address in it is a register plus an immediate
+  auto step_at = [&](auto pos_tag, int u, auto full) __attribute__((always_inline)) {
+    constexpr int P = decltype(pos_tag)::value;
+    mem_phase(std::integral_constant<int, P & 1>{}, u, (P / 2) % kASlots, P % kBSlots, (P / 2 + 2) % kASlots,
+              (P + 3) % kBSlots, full);
+    phase_barrier();
+    compute_phase();
   };
-  // steps 0 .. full_steps-1 lie wholly inside K; a trip is "full" if everything it fetches does
-  // (A double t/2+2 = steps t+4, t+5; B steps t+3, t+4)
+  auto step_pair = [&](int t, auto full) __attribute__((always_inline)) {   // t even; slots from t at run time
+    const int d = t >> 1;
+    mem_phase(std::integral_constant<int, 0>{}, t, d % kASlots, t % kBSlots, (d + 2) % kASlots, (t + 3) % kBSlots, full);
+    phase_barrier();
+    compute_phase();
+    mem_phase(std::integral_constant<int, 1>{}, t + 1, d % kASlots, (t + 1) % kBSlots, (d + 2) % kASlots, (t + 4) % kBSlots, full);
+    phase_barrier();
+    compute_phase();
+  };
+  // steps 0 .. full_steps-1 lie wholly inside K; a step is fetched unpredicated if everything the
+  // block it belongs to fetches lies inside K (step u fetches A double u/2+2 and B step u+3)
   const int full_steps = K / kStepK;
+  constexpr int CYCLE = 2 * kASlots * kBSlots / 2;               // lcm(2*kASlots, kBSlots) = 12 for rings of 3 and 4
+  static_assert(CYCLE % (2 * kASlots) == 0 && CYCLE % kBSlots == 0, "slot cycle");
   int t = 0;
+  for (; t + CYCLE + 4 <= full_steps; t += CYCLE)
+    for_each_index([&](auto pos) __attribute__((always_inline)) { step_at(pos, t + decltype(pos)::value, kFull); },
+                   std::make_integer_sequence<int, CYCLE>{});
   for (; t + 6 <= full_steps; t += 2) step_pair(t, kFull);
   for (; t < KT; t += 2) step_pair(t, kTail);
+  if (grp == 0) phase_barrier();                                 // group 1's last compute phase
 
   // ---- epilogue: fp32 -> bf16 (nearest even), transpose through a wave-private LDS patch ----
   wait_vmcnt<0>();   // the zero-filled look-ahead steps have landed too

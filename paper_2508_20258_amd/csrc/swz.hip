@@ -365,7 +365,7 @@ int swz_gemm_ex(const void* A, const void* B, void* C, int64_t M, int64_t N, int
   st = check_map_args(grid_m, grid_n, r.num_xcd, &group_m, mode);
   if (st != SWZ_OK) return st;
   if (r.bm == 128)
-    return launch_gemm<swz::GemmShape<128, 128, 2, 2>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
+    return launch_gemm<swz::GemmShape<128, 128, 2, 4>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
                                                                group_m, mode, r.num_wg, stream, 0);
   return launch_gemm<swz::GemmShape<256, 256, 2, 4>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
                                                              group_m, mode, r.num_wg, stream, 1);
