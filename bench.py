@@ -95,6 +95,23 @@ def time_calls(torch, fn, n=20):
     return e0.elapsed_time(e1) * 1e3 / n
 
 
+def measured_mfma_peak(swz, torch):
+    """Sustained rate of back-to-back independent MFMAs on register operands (no memory traffic), all CUs busy:
+    what the matrix cores deliver on this device at the clock the data lets it hold."""
+    out = torch.empty(512 * 1024, dtype=torch.float32, device="cuda")
+    res = {}
+    for name, rnd in (("random_operands", True), ("zero_operands", False)):
+        swz.mfma_peak(out, 2000, rnd)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flop = swz.mfma_peak(out, 20000, rnd)
+        e1.record()
+        torch.cuda.synchronize()
+        res[name] = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    return res
+
+
 def other_kernels(swz, torch):
     """The paper's other kernels built here (transpose, row softmax, layer normalisation): round-robin against the
     remapped program ids, GB/s of the algorithmic 4*M*N bytes against the 8 TB/s HBM roofline."""
@@ -233,6 +250,9 @@ def main():
 
     if not args.no_extras:
         out["other_kernels"] = other_kernels(swz, torch)
+        peak = measured_mfma_peak(swz, torch)
+        out["measured_mfma_peak_tflops"] = peak
+        out["pct_measured_mfma_peak"] = 100.0 * tflops / peak["random_operands"]
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(a_bits, b_bits, args.cpu_rows or M)

@@ -173,6 +173,17 @@ int swz_layernorm(const void* in, const void* gamma, const void* beta, void* out
  * Asynchronous on `stream`.  Errors: INVALID_ARG (null, bytes < 16), UNSUPPORTED (alignment), HIP. */
 int swz_copy_bytes(const void* src, void* dst, int64_t bytes, hipStream_t stream);
 
+/* Measurement aid, not part of the GEMM path: the matrix-core rate the device sustains with nothing
+ * else going on, against which the GEMM's TFLOP/s can be read beside the data-sheet peak.  Launches
+ * one 512-thread workgroup per compute unit; every wave issues iters x 64 independent
+ * v_mfma_f32_16x16x32_bf16 (16384 flop each) on register operands: pseudo-random bfloat16 values if
+ * random_operands != 0, zeros otherwise (the clock the chip sustains depends on the data).
+ * Flop per launch = *workgroups x 8 x iters x 64 x 16384.
+ *   out : DEVICE buffer of out_floats >= 512 x (number of compute units) floats; receives one
+ *         value per thread (the kernel's only memory traffic).   workgroups : HOST, may be null.
+ * Asynchronous on `stream`.  Errors: INVALID_ARG (null, iters < 1, buffer too small), HIP. */
+int swz_mfma_peak(float* out, int64_t out_floats, int iters, int random_operands, int* workgroups, hipStream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

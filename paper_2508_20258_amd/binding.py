@@ -18,7 +18,7 @@ DTYPE_BF16 = 0
 
 EXPORTS = ("swz_status_string", "swz_device_info", "swz_pid_map", "swz_pid_map_device", "swz_gemm", "swz_gemm_ex",
            "swz_gemm_plan", "swz_copy_bytes", "swz_pid_map_persistent", "swz_pid_map_persistent_device", "swz_transpose",
-           "swz_softmax", "swz_layernorm")
+           "swz_softmax", "swz_layernorm", "swz_mfma_peak")
 
 
 class SwzParams(ctypes.Structure):
@@ -53,7 +53,7 @@ def _load() -> ctypes.CDLL:
     _ensure_hip_runtime()
     if not os.path.exists(LIB_PATH):
         raise ImportError(
-            f"{LIB_PATH} is missing: build it with `python -m paper_2508_20258_amd.build` "
+            f"{LIB_PATH} is missing: build it with `python paper_2508_20258_amd/build.py` "
             "(hipcc, gfx950). There is no fallback path.")
     L = ctypes.CDLL(LIB_PATH)
     i, i64, vp = ctypes.c_int, ctypes.c_int64, ctypes.c_void_p
@@ -71,6 +71,7 @@ def _load() -> ctypes.CDLL:
     L.swz_transpose.argtypes = [vp, vp, i64, i64, i, i, i, pp, vp]
     L.swz_softmax.argtypes = [vp, vp, i64, i64, i, i, pp, vp]
     L.swz_layernorm.argtypes = [vp, vp, vp, vp, i64, i64, ctypes.c_float, i, i, pp, vp]
+    L.swz_mfma_peak.argtypes = [vp, i64, i, i, ip, vp]
     L.swz_pid_map_persistent.argtypes = [i, i, i, i, i, i, vp]
     L.swz_pid_map_persistent_device.argtypes = [i, i, i, i, i, i, vp, vp, vp]
     for name in EXPORTS:
@@ -237,3 +238,13 @@ def layernorm(x, gamma, beta, out=None, eps: float = 1e-5, chunks: int = 1, mode
     _check(lib.swz_layernorm(x.data_ptr(), gamma.data_ptr(), beta.data_ptr(), out.data_ptr(), x.shape[0], x.shape[1],
                              float(eps), int(chunks), int(mode), ctypes.byref(p), _stream_handle(stream)), "swz_layernorm")
     return out
+
+
+def mfma_peak(out, iters: int, random_operands: bool = True, stream=None) -> int:
+    """Launch the MFMA-rate measurement kernel (swz_mfma_peak); returns the flop count of the launch."""
+    import torch
+    assert out.is_cuda and out.is_contiguous() and out.dtype == torch.float32
+    wgs = ctypes.c_int(0)
+    _check(lib.swz_mfma_peak(out.data_ptr(), out.numel(), int(iters), int(bool(random_operands)), ctypes.byref(wgs),
+                             _stream_handle(stream)), "swz_mfma_peak")
+    return wgs.value * 8 * int(iters) * 64 * 16384

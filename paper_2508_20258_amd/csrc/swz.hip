@@ -7,6 +7,7 @@
 
 #include "../../include/swz.h"
 #include "gemm_kernel.h"
+#include "mfma_peak_kernel.h"
 #include "pid_decode.h"
 #include "rowwise_kernel.h"
 #include "transpose_kernel.h"
@@ -329,6 +330,17 @@ int swz_layernorm(const void* in, const void* gamma, const void* beta, void* out
   SWZ_LAUNCH_BY_PLAN(swz::layernorm_rows_kernel, static_cast<const uint16_t*>(in), static_cast<const uint16_t*>(gamma),
                      static_cast<const uint16_t*>(beta), static_cast<uint16_t*>(out), (int)M, (int)N, eps, chunks,
                      plan.chunk_vecs, plan.num_xcd, plan.group_m)
+  return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
+}
+
+int swz_mfma_peak(float* out, int64_t out_floats, int iters, int random_operands, int* workgroups, hipStream_t stream) {
+  if (out == nullptr || iters < 1) return SWZ_ERR_INVALID_ARG;
+  DeviceFacts f;
+  const int st = query_device(&f);
+  if (st != SWZ_OK) return st;
+  if (out_floats < (int64_t)f.cus * 512) return SWZ_ERR_INVALID_ARG;
+  if (workgroups != nullptr) *workgroups = f.cus;
+  hipLaunchKernelGGL(swz::mfma_peak_kernel, dim3((unsigned)f.cus), dim3(512), 0, stream, out, iters, random_operands ? 1 : 0);
   return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
 }
 

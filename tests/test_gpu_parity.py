@@ -321,3 +321,20 @@ def test_transpose_error_paths(swz):
     assert L.swz_transpose(None, y.data_ptr(), 64, 64, 2, 64, 0, None, s) == -1
     torch.cuda.synchronize()
     assert (y == 2.0).all()
+
+
+# ---------------------------------------------------------------------------- measurement aids
+
+def test_mfma_peak_kernel_runs_and_checks_its_buffer(swz):
+    info = swz.device_info()
+    out = torch.full((info["compute_units"] * 512,), float("nan"), dtype=torch.float32, device="cuda")
+    flop = swz.mfma_peak(out, 10, True)
+    torch.cuda.synchronize()
+    assert flop == info["compute_units"] * 8 * 10 * 64 * 16384 and torch.isfinite(out).all()
+    swz.mfma_peak(out, 10, False)
+    torch.cuda.synchronize()
+    assert (out == 0).all()                                   # zero operands: every accumulator stays 0
+    s = torch.cuda.current_stream().cuda_stream
+    assert swz.lib.swz_mfma_peak(out.data_ptr(), out.numel() - 1, 10, 1, None, s) == -1     # buffer too small
+    assert swz.lib.swz_mfma_peak(out.data_ptr(), out.numel(), 0, 1, None, s) == -1
+    assert swz.lib.swz_mfma_peak(None, out.numel(), 10, 1, None, s) == -1

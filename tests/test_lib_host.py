@@ -18,7 +18,7 @@ def test_library_exports_every_declared_entry_point():
     declared = set(re.findall(r"\b(swz_[a-z_]+)\s*\(", header))
     assert declared == {"swz_status_string", "swz_device_info", "swz_pid_map", "swz_pid_map_device", "swz_gemm",
                         "swz_gemm_ex", "swz_gemm_plan", "swz_copy_bytes", "swz_pid_map_persistent",
-                        "swz_pid_map_persistent_device", "swz_transpose", "swz_softmax", "swz_layernorm"}
+                        "swz_pid_map_persistent_device", "swz_transpose", "swz_softmax", "swz_layernorm", "swz_mfma_peak"}
     raw = ctypes.CDLL(swz.binding.LIB_PATH)
     for name in declared:
         assert hasattr(raw, name), name
@@ -135,3 +135,15 @@ def test_persistent_error_paths():
     assert (p["persistent"], p["num_wg"]) == (0, 0)
     with pytest.raises(swz.SwzError):
         swz.gemm_plan(512, 512, 512, num_xcd=8, persistent=2)
+
+
+def test_build_script_runs_without_importing_the_package():
+    # the package refuses to import without libswz.so, so the build entry must not depend on importing it
+    import importlib.util
+    path = os.path.join(ROOT, "paper_2508_20258_amd", "build.py")
+    spec = importlib.util.spec_from_file_location("swz_build_under_test", path)
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    assert mod.build(force=False) == swz.binding.LIB_PATH          # up to date: returns without compiling
+    entry = open(os.path.join(ROOT, "__graft_entry__.py")).read()
+    assert "from paper_2508_20258_amd.build import" not in entry
