@@ -108,10 +108,13 @@ def test_ragged_shapes_full_matrix(swz, tile, M, N, K):
         assert np.array_equal(c, outs[0])
 
 
-@pytest.mark.parametrize("K", [8, 24, 32, 40, 64, 96, 104, 128, 136, 160, 168, 200, 232, 264, 1000])
+@pytest.mark.parametrize("K", [8, 24, 32, 40, 64, 96, 104, 128, 136, 160, 168, 200, 232, 264, 1000,
+                               # 16 steps and more: the 12-step unrolled body engages; one and two passes of it, with
+                               # every kind of remainder (none, runtime-slot steps, predicated steps, partial step)
+                               480, 512, 520, 544, 576, 640, 736, 864, 896, 904, 1280, 1312])
 def test_every_k_tail_and_pipeline_depth(swz, K):
     # K steps of 32: fewer steps than ring stages, odd and even step counts, partial last step,
-    # and the hand-over between the unpredicated and the predicated load path
+    # and the hand-overs between the unrolled, the unpredicated and the predicated load paths
     M, N = 272, 264
     a = si.matrix_bf16(300 + K, 0, M, K, "normal")
     b = si.matrix_bf16(300 + K, 1, K, N, "uniform")
