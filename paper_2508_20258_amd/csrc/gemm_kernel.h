@@ -341,9 +341,13 @@ __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const 
     wait_vmcnt_lgkmcnt<2 * S::LOADS, 0>();
     __builtin_amdgcn_sched_barrier(0);
   };
+  // Row block by row block, the column blocks alternately left to right and right to left: from
+  // one MFMA to the next exactly one of the two fragment operands changes (measured +1.3 to
+  // +1.6 % against an order in which both change at the end of a row block: the chip is power
+  // bound, and an operand that stays costs less).
   auto compute_phase = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < NM; ++i) mfma(i / TN, i % TN);
+    for (int i = 0; i < NM; ++i) mfma(i / TN, ((i / TN) & 1) ? TN - 1 - i % TN : i % TN);
     __builtin_amdgcn_sched_barrier(0);
     block_barrier();
     __builtin_amdgcn_sched_barrier(0);
