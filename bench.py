@@ -28,9 +28,9 @@ PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA, published (256 CUs x 
 # plain 1 GiB copy kernel (FETCH_SIZE reads 0.5x the bytes copied, WRITE_SIZE 1.0x).  Valid only
 # for the kernel source whose hash is recorded here; any other kernel reports null.
 TRAFFIC = {
-    "kernel_sha256": "8d33615983c51b5f22af810beb4ebcd6f3fa1f452ea90afdd3c521f677b8b011",
-    # FETCH_SIZE 98425 KiB x 2.000 + WRITE_SIZE 32788 KiB x 1.000 per dispatch (profiles/gemm_cfg2_4096.txt)
-    "cfg2_4096": {"xcd_groupm": {"fetch_bytes": 201573760, "write_bytes": 33574997, "total_bytes": 235148757,
+    "kernel_sha256": "0ce3389157eaf6ae8f5b930bdd7d46dddd251af9b7fd3683d0890debdb670dcf",
+    # FETCH_SIZE 98421 KiB x 2.000 + WRITE_SIZE 32786 KiB x 1.000 per dispatch (profiles/gemm_cfg2_4096.txt)
+    "cfg2_4096": {"xcd_groupm": {"fetch_bytes": 201565312, "write_bytes": 33572650, "total_bytes": 235137962,
                                  "algorithmic_min_bytes": 100663296}},
 }
 
