@@ -124,7 +124,7 @@ def other_kernels(swz, torch):
     m = n = 16384
     x = torch.randint(-32768, 32767, (m, n), dtype=torch.int16, device="cuda").view(torch.bfloat16)
     y = torch.empty((n, m), dtype=torch.bfloat16, device="cuda")
-    for tile in (64, 32):
+    for tile in (128, 64, 32):
         for mode in ("rr", "xcd_groupm"):
             us = time_calls(torch, lambda: swz.transpose(x, y, tile=tile, mode=swz.MODES[mode]))
             res[f"transpose_{m}x{n}_tile{tile}_{mode}"] = entry(us, m, n)

@@ -131,10 +131,11 @@ int swz_gemm_plan(int64_t M, int64_t N, int64_t K, const swz_params* params, swz
  * grid is ceil(M/tile) x ceil(N/tile) and hardware workgroup ids are turned into tiles exactly as
  * swz_pid_map does for that grid (`mode`, params->group_m, params->num_xcd; other fields ignored).
  *   in, out : caller-owned DEVICE pointers, 16-byte aligned, must not overlap.
- *   tile    : 64 (row segments are whole 128-byte lines) or 32 (half lines, shared between
- *             neighbouring tiles: the case where the mapping decides the L2 hit rate).
+ *   tile    : 128 (row segments of 256 bytes, the fastest), 64 (whole 128-byte lines) or 32 (half
+ *             lines, shared between neighbouring tiles: the case where the mapping decides the L2
+ *             hit rate).
  * Asynchronous on `stream`; never allocates or synchronises.
- * Errors: INVALID_ARG (null, M/N < 1, unknown mode), UNSUPPORTED (elem_bytes != 2, tile not 32/64,
+ * Errors: INVALID_ARG (null, M/N < 1, unknown mode), UNSUPPORTED (elem_bytes != 2, tile not 32/64/128,
  * M or N not a multiple of 8, misaligned pointer), OVERFLOW, HIP. */
 int swz_transpose(const void* in, void* out, int64_t M, int64_t N, int elem_bytes, int tile, int mode,
                   const swz_params* params, hipStream_t stream);

@@ -197,7 +197,7 @@ def pid_map_persistent_device(grid_m: int, grid_n: int, num_xcd: int, group_m: i
     return tile, xcc
 
 
-def transpose(x, out=None, tile: int = 64, mode: int = MODE_XCD_GROUPM, stream=None, **params):
+def transpose(x, out=None, tile: int = 128, mode: int = MODE_XCD_GROUPM, stream=None, **params):
     """out (N x M) = x (M x N) transposed on the GPU through swz_transpose; 16-bit element tensors."""
     import torch
     assert x.is_cuda and x.is_contiguous() and x.dim() == 2 and x.element_size() == 2

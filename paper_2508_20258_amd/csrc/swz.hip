@@ -282,7 +282,7 @@ int swz_transpose(const void* in, void* out, int64_t M, int64_t N, int elem_byte
   if (in == nullptr || out == nullptr || M < 1 || N < 1 || !valid_mode(mode)) return SWZ_ERR_INVALID_ARG;
   const int64_t lim = (int64_t)1 << 31;
   if (M >= lim || N >= lim) return SWZ_ERR_OVERFLOW;
-  if (elem_bytes != 2 || (tile != 32 && tile != 64) || (M % 8) != 0 || (N % 8) != 0) return SWZ_ERR_UNSUPPORTED;
+  if (elem_bytes != 2 || (tile != 32 && tile != 64 && tile != 128) || (M % 8) != 0 || (N % 8) != 0) return SWZ_ERR_UNSUPPORTED;
   if ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) return SWZ_ERR_UNSUPPORTED;
   int group_m = 4, num_xcd = 0;
   if (params != nullptr) {
@@ -300,6 +300,7 @@ int swz_transpose(const void* in, void* out, int64_t M, int64_t N, int elem_byte
   if (gm * gn >= lim) return SWZ_ERR_OVERFLOW;
   const int st = check_map_args((int)gm, (int)gn, num_xcd, &group_m, mode);
   if (st != SWZ_OK) return st;
+  if (tile == 128) return launch_transpose<128>(in, out, (int)M, (int)N, (int)gm, (int)gn, num_xcd, group_m, mode, stream);
   return tile == 64 ? launch_transpose<64>(in, out, (int)M, (int)N, (int)gm, (int)gn, num_xcd, group_m, mode, stream)
                     : launch_transpose<32>(in, out, (int)M, (int)N, (int)gm, (int)gn, num_xcd, group_m, mode, stream);
 }

@@ -295,7 +295,7 @@ def main(argv=None):
     t = sub.add_parser("transpose")
     t.add_argument("--m", type=int, default=16384)
     t.add_argument("--n", type=int, default=16384)
-    t.add_argument("--tile", type=int, default=64, choices=[32, 64])
+    t.add_argument("--tile", type=int, default=128, choices=[32, 64, 128])
     t.add_argument("--mode", default="xcd_groupm", choices=["rr", "xcd", "xcd_groupm", "groupm"])
     t.add_argument("--launches", type=int, default=10)
     t.set_defaults(fn=cmd_transpose)

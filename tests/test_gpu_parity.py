@@ -295,7 +295,7 @@ def test_persistent_full_size_cfg5_is_bit_identical(swz):
 
 # ---------------------------------------------------------------------------- transpose (bit-exact)
 
-@pytest.mark.parametrize("tile", [32, 64])
+@pytest.mark.parametrize("tile", [32, 64, 128])
 @pytest.mark.parametrize("M,N", [(8, 8), (64, 64), (200, 328), (1000, 72), (2048, 1024), (4104, 520)])
 def test_transpose_is_bit_exact_in_every_mode(swz, tile, M, N):
     from oracle import transpose_ref
