@@ -123,17 +123,18 @@ def cmd_transpose(args):
     x = torch.randint(-32768, 32767, (args.m, args.n), dtype=torch.int16, device="cuda").view(torch.bfloat16)
     out = torch.empty((args.n, args.m), dtype=torch.bfloat16, device="cuda")
     mode = swz.MODES[args.mode]
-    swz.transpose(x, out, tile=args.tile, mode=mode)
+    params = dict(group_m=args.group_m) if args.group_m else {}
+    swz.transpose(x, out, tile=args.tile, mode=mode, **params)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(max(args.launches - 1, 1)):
-        swz.transpose(x, out, tile=args.tile, mode=mode)
+        swz.transpose(x, out, tile=args.tile, mode=mode, **params)
     e1.record()
     torch.cuda.synchronize()
     us = e0.elapsed_time(e1) * 1e3 / max(args.launches - 1, 1)
     gbs = 4.0 * args.m * args.n / (us * 1e-6) / 1e9
-    print(f"ran {args.launches} transposes {args.m}x{args.n} tile {args.tile} mode {args.mode}: {us:.2f} us per launch, "
+    print(f"ran {args.launches} transposes {args.m}x{args.n} tile {args.tile} mode {args.mode} group_m {args.group_m or 4}: {us:.2f} us per launch, "
           f"{gbs:.0f} GB/s of 4*M*N bytes ({100 * gbs / 8000:.1f} % of 8 TB/s)", flush=True)
 
 
@@ -298,6 +299,7 @@ def main(argv=None):
     t.add_argument("--tile", type=int, default=128, choices=[32, 64, 128])
     t.add_argument("--mode", default="xcd_groupm", choices=["rr", "xcd", "xcd_groupm", "groupm"])
     t.add_argument("--launches", type=int, default=10)
+    t.add_argument("--group-m", type=int, default=0)
     t.set_defaults(fn=cmd_transpose)
     w = sub.add_parser("rows")
     w.add_argument("--op", default="softmax", choices=["softmax", "layernorm"])
