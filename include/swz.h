@@ -27,7 +27,7 @@ typedef struct ihipStream_t* hipStream_t;
 typedef enum {
   SWZ_OK = 0,
   SWZ_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, unknown mode                */
-  SWZ_ERR_UNSUPPORTED = -2, /* valid request this build cannot serve (dtype, alignment, tile) */
+  SWZ_ERR_UNSUPPORTED = -2, /* valid request the library cannot serve (dtype, alignment, tile) */
   SWZ_ERR_OVERFLOW = -3,    /* a count does not fit the 32-bit index arithmetic              */
   SWZ_ERR_HIP = -4          /* the HIP runtime reported an error (launch, attribute query)   */
 } swz_status;
