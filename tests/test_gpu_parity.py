@@ -326,6 +326,16 @@ def test_transpose_error_paths(swz):
     assert (y == 2.0).all()
 
 
+@pytest.mark.parametrize("M,N,K", [(1300, 1096, 200), (520, 776, 96), (2100, 2064, 544)])
+def test_tile_shape_does_not_change_the_bits(swz, M, N, K):
+    # every element of C is accumulated over the same K steps in the same order whatever the tile shape
+    a = si.matrix_bf16(900 + M, 0, M, K, "normal")
+    b = si.matrix_bf16(900 + M, 1, K, N, "uniform")
+    big = run_modes(swz, a, b, modes=(2,), bm=256, bn=256)[2]
+    small = run_modes(swz, a, b, modes=(0,), bm=128, bn=128)[0]
+    assert np.array_equal(big, small)
+
+
 # ---------------------------------------------------------------------------- measurement aids
 
 def test_mfma_peak_kernel_runs_and_checks_its_buffer(swz):
