@@ -189,13 +189,17 @@ def _rows(path):
 
 
 def summarize(directory, kernel_filter=None):
-    """Returns {kernel name: {"n": dispatches, "avg_ns": ..., "counters": {name: avg per dispatch}}}."""
-    out = defaultdict(lambda: {"n": 0, "total_ns": 0, "counters": defaultdict(float), "counter_n": defaultdict(int)})
+    """Returns {kernel name: {"n": dispatches, "avg_ns": ..., "warm_avg_ns": ..., "counters": {name: avg per dispatch}}}.
+
+    warm_avg_ns is the average over the later half of the dispatches in start order: a run started on an idle
+    device spends its first launches ramping the clock up."""
+    out = defaultdict(lambda: {"n": 0, "total_ns": 0, "spans": [], "counters": defaultdict(float), "counter_n": defaultdict(int)})
     for path in glob.glob(os.path.join(directory, "**", "*kernel_trace.csv"), recursive=True):
         for r in _rows(path):
             k = r["Kernel_Name"]
             out[k]["n"] += 1
             out[k]["total_ns"] += int(r["End_Timestamp"]) - int(r["Start_Timestamp"])
+            out[k]["spans"].append((int(r["Start_Timestamp"]), int(r["End_Timestamp"]) - int(r["Start_Timestamp"])))
     for path in glob.glob(os.path.join(directory, "**", "*counter_collection.csv"), recursive=True):
         per_dispatch = defaultdict(float)
         for r in _rows(path):
@@ -207,7 +211,9 @@ def summarize(directory, kernel_filter=None):
     for k, d in out.items():
         if kernel_filter and kernel_filter not in k:
             continue
+        late = [dur for _, dur in sorted(d["spans"])][len(d["spans"]) // 2:]
         res[k] = {"n": d["n"], "avg_ns": d["total_ns"] / d["n"] if d["n"] else None,
+                  "warm_avg_ns": sum(late) / len(late) if late else None,
                   "counters": {c: d["counters"][c] / d["counter_n"][c] for c in d["counters"]}}
     return res
 

@@ -19,6 +19,7 @@ def test_csv_summary(tmp_path):
     assert list(r) == ["gemm<2>"]
     g = r["gemm<2>"]
     assert g["n"] == 2 and g["avg_ns"] == 1500
+    assert g["warm_avg_ns"] == 1000                             # the later half of the dispatches: the second one
     assert g["counters"]["TCC_HIT_sum"] == 40 and g["counters"]["TCC_MISS_sum"] == 10
     assert g["counters"]["FETCH_SIZE"] == 10.0
 
