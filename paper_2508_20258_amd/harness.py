@@ -5,6 +5,7 @@ reader that turns rocprofv3's CSV output into the summaries kept with the measur
     python -m paper_2508_20258_amd.harness copy --mib 1024 --launches 3
     python -m paper_2508_20258_amd.harness transpose --m 16384 --n 16384 --tile 32 --mode rr
     python -m paper_2508_20258_amd.harness rows --op softmax --m 8192 --n 8192 --chunks 8 --mode xcd
+    python -m paper_2508_20258_amd.harness peak
     python -m paper_2508_20258_amd.harness summarize <rocprofv3 output dir>
     python -m paper_2508_20258_amd.harness rank --workload cfg4_skinny
 
@@ -169,6 +170,30 @@ def cmd_rows(args):
           f"{gbs:.0f} GB/s of 4*M*N bytes ({100 * gbs / 8000:.1f} % of 8 TB/s)", flush=True)
 
 
+def cmd_peak(args):
+    """Data-sheet MFMA peak from the device's unit counts, and the rate the device sustains on register operands."""
+    import torch
+
+    import paper_2508_20258_amd as swz
+    info = swz.device_info()
+    cus = info["compute_units"]
+    sheet = cus * 4 * 1024 * 2.4e9 / 1e12
+    print(f"data sheet: {cus} CUs x 4 SIMDs x 1024 flop/clk (one 16x16x32 bf16 MFMA = 16384 flop per 16 clocks) x 2.4 GHz "
+          f"= {sheet:.1f} TFLOP/s (published: 2.5 PFLOP/s dense bf16)")
+    out = torch.empty(cus * 512, dtype=torch.float32, device="cuda")
+    for name, rnd in (("zero operands", False), ("random bf16 operands", True)):
+        swz.mfma_peak(out, 2000, rnd)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flop = swz.mfma_peak(out, args.iters, rnd)
+        e1.record()
+        torch.cuda.synchronize()
+        t = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        print(f"measured, {name}: {t:.1f} TFLOP/s = {100 * t / sheet:.1f} % of the data-sheet figure "
+              f"(sustained clock ~{2.4 * t / sheet:.2f} GHz if every SIMD issues back to back)", flush=True)
+
+
 def cmd_copy(args):
     import torch
 
@@ -315,6 +340,9 @@ def main(argv=None):
     w.add_argument("--mode", default="xcd", choices=["rr", "xcd", "xcd_groupm", "groupm"])
     w.add_argument("--launches", type=int, default=10)
     w.set_defaults(fn=cmd_rows)
+    pk = sub.add_parser("peak")
+    pk.add_argument("--iters", type=int, default=20000)
+    pk.set_defaults(fn=cmd_peak)
     c = sub.add_parser("copy")
     c.add_argument("--mib", type=int, default=1024)
     c.add_argument("--launches", type=int, default=3)
