@@ -336,6 +336,31 @@ def test_tile_shape_does_not_change_the_bits(swz, M, N, K):
     assert np.array_equal(big, small)
 
 
+def _random_shapes():
+    rng = np.random.default_rng(20258)
+    shapes = []
+    for _ in range(10):
+        M = int(rng.integers(1, 900))
+        N = 8 * int(rng.integers(1, 110))
+        K = 8 * int(rng.integers(1, 420))          # up to 105 steps of 32: many passes of the unrolled loop body
+        shapes.append((M, N, K))
+    return shapes
+
+
+@pytest.mark.parametrize("M,N,K", _random_shapes())
+def test_random_shapes_full_matrix(swz, M, N, K):
+    a = si.matrix_bf16(1000 + K, 0, M, K, "normal")
+    b = si.matrix_bf16(1000 + K, 1, K, N, "normal", 1.0 / np.sqrt(K))
+    ref = gemm_ref.gemm(a, b)
+    big = run_modes(swz, a, b, modes=(0, 2), bm=256, bn=256)
+    assert_within_tolerance(big[2], ref, f"{M}x{N}x{K} tile 256")
+    assert np.array_equal(big[0], big[2])
+    small = run_modes(swz, a, b, modes=(1,), bm=128, bn=128)[1]
+    assert np.array_equal(small, big[2])
+    pers = run_modes(swz, a, b, modes=(3,), persistent=1, num_wg=5)[3]
+    assert np.array_equal(pers, big[2])
+
+
 # ---------------------------------------------------------------------------- measurement aids
 
 def test_mfma_peak_kernel_runs_and_checks_its_buffer(swz):
