@@ -122,11 +122,39 @@ def xcd_tile_sets(out, num_xcd: int) -> list[list[int]]:
     return [[int(out[w]) for w in bucket] for bucket in deal_round_robin(len(out), num_xcd)]
 
 
-def fair_share(out, num_xcd: int) -> bool:
-    """XCD x computes floor(T/X) tiles, plus one if x < T mod X."""
-    t = len(out)
-    return all(len(s) == t // num_xcd + (1 if x < t % num_xcd else 0)
-               for x, s in enumerate(xcd_tile_sets(out, num_xcd)))
+def fair_share(out, grid_m: int, grid_n: int, group_m: int, grouped: bool, num_xcd: int, renumbered: bool) -> bool:
+    """Every XCD works on its fair share of the raster, judged on the map itself.
+
+    The tile count T comes from the grid, never from len(out).  XCD x (the workgroups w with
+    w mod X == x) must hold T div X distinct raster positions, one more if x < T mod X; the shares of
+    different XCDs must not overlap and together they must be the whole raster.  For a renumbering
+    map (renumbered=True) XCD x's share must moreover begin right where the shares of XCDs 0..x-1
+    end ("all contiguous blocks on the same XCD before moving to the next XCD").
+    A map of the wrong length, a tile outside the grid, a tile handed out twice, or an XCD that
+    holds a position of another XCD's share all fail.
+    """
+    total = grid_m * grid_n
+    order = raster_order(grid_m, grid_n, group_m, grouped)
+    pos = {pm * grid_n + pn: l for l, (pm, pn) in enumerate(order)}
+    if len(out) != total:
+        return False
+    claimed: set[int] = set()
+    begin = 0                                   # where XCD x's share begins if shares are laid end to end
+    for x in range(num_xcd):
+        want = total // num_xcd + (1 if x < total % num_xcd else 0)
+        share = set()
+        for w in range(x, len(out), num_xcd):
+            t = int(out[w])
+            if t not in pos:
+                return False
+            share.add(pos[t])
+        if len(share) != want or share & claimed:
+            return False
+        if renumbered and want > 0 and min(share) != begin:
+            return False
+        claimed |= share
+        begin += want
+    return len(claimed) == total
 
 
 def xcd_runs_contiguous(out, grid_m: int, grid_n: int, group_m: int, grouped: bool, num_xcd: int) -> bool:

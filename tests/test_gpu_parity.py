@@ -68,6 +68,29 @@ def test_hardware_dispatch_is_round_robin_over_xcds(swz):
         assert (xcc == first[np.arange(xcc.size) % X]).all()              # workgroup w runs on XCD (w mod X)
 
 
+@pytest.mark.parametrize("gm,gn", [(79, 55), (5, 5), (7, 3), (40, 28)])
+def test_every_xcd_really_gets_its_fair_share(swz, gm, gn):
+    # counted from the XCD each workgroup reports it ran on (hardware register), not from the dispatch model
+    X = swz.device_info()["num_xcd"]
+    T = gm * gn
+    for mode in range(4):
+        tile, xcc = swz.pid_map_device(gm, gn, X, 4, mode)
+        torch.cuda.synchronize()
+        tile, xcc = tile.cpu().numpy(), xcc.cpu().numpy()
+        label = xcc[:X] if T >= X else xcc                  # physical id of the XCD that serves w mod X == x
+        for x in range(min(X, T)):
+            mine = tile[xcc == label[x]]
+            assert mine.size == T // X + (1 if x < T % X else 0), (mode, x)
+        assert opm.fair_share(tile.tolist(), gm, gn, 4, mode in (2, 3), X, mode in (1, 2))
+        if mode in (1, 2):
+            # what one physical XCD computed is one unbroken stretch of the raster
+            order = opm.raster_order(gm, gn, 4, mode == 2)
+            pos = {pm * gn + pn: l for l, (pm, pn) in enumerate(order)}
+            for x in range(min(X, T)):
+                ps = sorted(pos[int(t)] for t in tile[xcc == label[x]])
+                assert ps == list(range(ps[0], ps[0] + len(ps)))
+
+
 def test_device_entry_point_error_paths(swz):
     t = torch.full((16,), -7, dtype=torch.int32, device="cuda")
     L = swz.lib

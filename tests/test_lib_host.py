@@ -44,7 +44,7 @@ def test_workload_grids_match_oracle_and_invariants(gm, gn, X, g):
     for mode in range(4):
         got = swz.pid_map(gm, gn, X, g, mode).tolist()
         assert got == opm.pid_map(gm, gn, X, g, mode)
-        assert opm.is_permutation(got, gm * gn) and opm.fair_share(got, X)
+        assert opm.is_permutation(got, gm * gn) and opm.fair_share(got, gm, gn, g, mode in (2, 3), X, mode in (1, 2))
         if mode in (1, 2):
             assert opm.xcd_runs_contiguous(got, gm, gn, g, mode == 2, X)
 

@@ -91,7 +91,7 @@ def test_invariants(gm, gn, X, mode):
     out = opm.pid_map(gm, gn, X, g, mode)
     T = gm * gn
     assert opm.is_permutation(out, T)
-    assert opm.fair_share(out, X)
+    assert opm.fair_share(out, gm, gn, g, mode in (2, 3), X, mode in (1, 2))
     if mode in (1, 2):
         assert opm.xcd_runs_contiguous(out, gm, gn, g, mode == 2, X)
     if mode == 2:
@@ -111,8 +111,63 @@ def test_checkers_catch_planted_mistakes():
     assert not opm.xcd_runs_contiguous(swapped, gm, gn, g, True, X)
     rr = opm.pid_map(gm, gn, X, g, 0)
     assert not opm.xcd_runs_contiguous(rr, gm, gn, g, False, X)   # round-robin scatters neighbours
-    lopsided = [t for w, t in enumerate(good) if w % X != 1]      # XCD 1 loses its workgroups
-    assert opm.fair_share(good, X) and len(lopsided) % X != 0
+
+
+def test_fair_share_checker_can_fail():
+    # Each planted map breaks the invariant in a different way; the checker must reject every one of them
+    # and accept the maps they were derived from.
+    gm, gn, X, g = 6, 5, 4, 2                      # T = 30 = 4*7 + 2: XCDs 0, 1 hold 8 raster positions, XCDs 2, 3 hold 7
+    T = gm * gn
+    for mode in range(4):
+        good = opm.pid_map(gm, gn, X, g, mode)
+        args = (gm, gn, g, mode in (2, 3), X)
+        assert opm.fair_share(good, *args, mode in (1, 2))
+        # XCD 0 is handed one of XCD 1's tiles (that tile is then computed twice, one of XCD 0's never)
+        stolen = list(good)
+        stolen[0] = good[1]
+        assert not opm.fair_share(stolen, *args, False)
+        # right length, not a permutation: a tile repeated inside one XCD's own share
+        repeated = list(good)
+        repeated[X] = good[0]
+        assert not opm.fair_share(repeated, *args, False)
+        # wrong lengths: an XCD loses its workgroups / a stray extra workgroup
+        lopsided = [t for w, t in enumerate(good) if w % X != 1]
+        assert not opm.fair_share(lopsided, *args, False)
+        assert not opm.fair_share(good + [good[0]], *args, False)
+        assert not opm.fair_share(good[:-1], *args, False)
+        # a tile outside the grid
+        outside = list(good)
+        outside[3] = T
+        assert not opm.fair_share(outside, *args, False)
+    # a permutation in which two XCDs trade a tile: counts are right, so the plain share check passes,
+    # but XCD 0's share no longer is the stretch of the raster that begins at 0 / XCD 1's at 8
+    good = opm.pid_map(gm, gn, X, g, 2)
+    traded = list(good)
+    traded[0], traded[1] = traded[1], traded[0]
+    assert opm.is_permutation(traded, T) and opm.fair_share(traded, gm, gn, g, True, X, False)
+    assert not opm.fair_share(traded, gm, gn, g, True, X, True)
+    # round-robin dispatch of the plain raster is fair in counts but no XCD's share begins where the previous ends
+    rr = opm.pid_map(gm, gn, X, g, 0)
+    assert opm.fair_share(rr, gm, gn, g, False, X, False) and not opm.fair_share(rr, gm, gn, g, False, X, True)
+    # the paper's printed ceil-form on a ragged count leaves [0, T) and must fail too
+    bad = [paper_printed_swizzle(w, 10, 8) for w in range(10)]
+    assert not opm.fair_share(bad, 2, 5, 1, False, 8, True)
+    # random lists of the right length (what the old length-only check accepted) fail
+    import random
+    rng = random.Random(5)
+    assert not any(opm.fair_share([rng.randrange(T) for _ in range(T)], gm, gn, g, False, X, False) for _ in range(50))
+
+
+@pytest.mark.parametrize("T,X", [(20, 4), (30, 4), (10, 8), (5, 8), (4345, 8), (25, 8), (7, 7)])
+def test_fair_share_sizes_against_brute_force_counts(T, X):
+    # the share sizes the checker demands, counted the slow way: deal T workgroups one at a time
+    counts = [0] * X
+    for w in range(T):
+        counts[w % X] += 1
+    out = opm.pid_map(1, T, X, 1, opm.MODE_XCD)
+    assert opm.fair_share(out, 1, T, 1, False, X, True)
+    for x, tiles in enumerate(opm.xcd_tile_sets(out, X)):
+        assert len(tiles) == counts[x] and tiles == list(range(sum(counts[:x]), sum(counts[:x + 1])))
 
 
 def test_bad_arguments_raise():

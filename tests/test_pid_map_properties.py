@@ -17,7 +17,7 @@ def test_one_workgroup_per_tile(gm, gn, X, g, m):
     got = swz.pid_map(gm, gn, X, g, m)
     assert got.tolist() == opm.pid_map(gm, gn, X, g, m)
     assert np.array_equal(np.sort(got), np.arange(gm * gn))          # bijection onto [0, T)
-    assert opm.fair_share(got.tolist(), X)
+    assert opm.fair_share(got.tolist(), gm, gn, g, m in (2, 3), X, m in (1, 2))
     if m in (1, 2):
         assert opm.xcd_runs_contiguous(got.tolist(), gm, gn, g, m == 2, X)
 
