@@ -53,11 +53,22 @@ typedef struct {
   int32_t num_wg;  /* persistent grid size (default: one workgroup per compute unit, at most one per tile) */
 } swz_params;
 
+/* Human-readable name of a swz_status (the pass/fail reporting of the paper's validation step,
+ * Methodology step 3, needs one).  Returns a static string, never null; unknown codes included. */
 const char* swz_status_string(int status);
 
-/* Facts about the current device that the remap depends on (the paper's "hardware context":
- * XCD count, CUs, L2 size).  Any pointer may be null.  num_xcd is derived from the gfx950 CU
- * count (32 CUs per XCD); l2_bytes is per XCD; lds_bytes is per workgroup. */
+/* Facts about the current device that the remap depends on (the paper's "hardware context" of
+ * Methodology step 2: XCD count, CUs, L2 size, taken from HIP device attributes).  Any pointer may
+ * be null.
+ *   num_xcd       : CU count / 32 (gfx950: 32 CUs per XCD; a partitioned device exposes fewer
+ *                   XCDs), or the value of the environment variable SWZ_NUM_XCD (an integer in
+ *                   1..1024, read once per process) when it is set; 0 if the CU count is not a
+ *                   whole number of XCDs and no override is given.  Entry points that default
+ *                   num_xcd then return SWZ_ERR_UNSUPPORTED until the caller names it.
+ *   compute_units : hipDeviceAttributeMultiprocessorCount.
+ *   l2_bytes      : hipDeviceAttributeL2CacheSize as the runtime reports it, unchanged (on an
+ *                   MI355X that is 4 MiB, the private L2 of ONE XCD, not the sum over XCDs).
+ *   lds_bytes     : hipDeviceAttributeMaxSharedMemoryPerBlock (LDS one workgroup may use). */
 int swz_device_info(int* num_xcd, int* compute_units, int* l2_bytes, int* lds_bytes);
 
 /* The PID map, computed on the host (GEMM swizzle of the paper's appendix, extended so that
@@ -72,7 +83,9 @@ int swz_device_info(int* num_xcd, int* compute_units, int* l2_bytes, int* lds_by
  * Errors: INVALID_ARG (null out, any argument < 1, unknown mode), OVERFLOW (grid_m*grid_n >= 2^31). */
 int swz_pid_map(int grid_m, int grid_n, int num_xcd, int group_m, int mode, int32_t* out);
 
-/* The same map evaluated by the DEVICE integer code the GEMM kernel uses: launches
+/* The same map (paper: GEMM appendix; the claim "workgroups are dealt round-robin to the XCDs" of
+ * the Introduction is what d_xcc lets a caller verify) evaluated by the DEVICE integer code the
+ * GEMM kernel uses: launches
  * grid_m*grid_n workgroups; workgroup w writes d_tile[w] = pm*grid_n + pn and, if d_xcc is
  * not null, d_xcc[w] = id of the XCD it actually ran on (hardware register XCC_ID).
  *   d_tile, d_xcc : caller-owned DEVICE buffers of grid_m*grid_n int32.
@@ -113,13 +126,17 @@ int swz_pid_map_persistent_device(int grid_m, int grid_n, int num_xcd, int group
 int swz_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,
              hipStream_t stream);
 
-/* swz_gemm with explicit tile shape / group_m / num_xcd / launch style (null params = all defaults).
+/* swz_gemm (paper: Appendix "Case Study: GEMM Swizzling") with explicit tile shape / group_m /
+ * num_xcd / launch style (null params = all defaults); persistent = 1 is the launch style of the
+ * paper's own listing (as many workgroups as compute units, each looping over tiles).
  * UNSUPPORTED for a tile shape other than 128x128x64 or 256x256x64.  The persistent launch computes
  * every tile with the same instruction sequence, so its C is bit-identical to the default launch. */
 int swz_gemm_ex(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,
                 const swz_params* params, hipStream_t stream);
 
-/* What swz_gemm_ex would launch for this problem: the resolved parameters and tile grid.
+/* What swz_gemm_ex would launch for this problem: the resolved parameters and tile grid, i.e. the
+ * arguments with which swz_pid_map reproduces the launch's map (the paper validates a remap by
+ * its map being a bijection: Results, "broken remappings").
  * Pure host arithmetic apart from the device query that resolves num_xcd = 0.
  * Any output pointer may be null. */
 int swz_gemm_plan(int64_t M, int64_t N, int64_t K, const swz_params* params, swz_params* resolved,

@@ -98,6 +98,17 @@ def _stream_handle(stream) -> int:
     return int(s.cuda_stream)
 
 
+def _same_current_device(stream, *tensors) -> None:
+    """The library launches on the calling thread's current device: every tensor must live there (and the stream too)."""
+    import torch
+    cur = torch.cuda.current_device()
+    for t in tensors:
+        if t.device.index != cur:
+            raise ValueError(f"tensor on cuda:{t.device.index} but the current device is cuda:{cur}")
+    if stream is not None and getattr(stream, "device", None) is not None and stream.device.index != cur:
+        raise ValueError(f"stream of cuda:{stream.device.index} but the current device is cuda:{cur}")
+
+
 def _params(bm=0, bn=0, bk=0, group_m=0, num_xcd=0, persistent=0, num_wg=0) -> SwzParams:
     return SwzParams(int(bm), int(bn), int(bk), int(group_m), int(num_xcd), int(persistent), int(num_wg))
 
@@ -154,6 +165,7 @@ def gemm(a, b, c=None, mode: int = MODE_XCD_GROUPM, stream=None, **params):
     if c is None:
         c = torch.empty((M, N), dtype=torch.bfloat16, device=a.device)
     assert c.is_cuda and c.dtype == torch.bfloat16 and c.is_contiguous() and tuple(c.shape) == (M, N)
+    _same_current_device(stream, a, b, c)
     h = _stream_handle(stream)
     if params:
         p = _params(**params)
@@ -168,6 +180,7 @@ def copy_bytes(src, dst, stream=None) -> None:
     """Plain device copy of src into dst (same byte size), the calibration kernel of known traffic."""
     nbytes = src.numel() * src.element_size()
     assert src.is_cuda and dst.is_cuda and dst.numel() * dst.element_size() == nbytes
+    _same_current_device(stream, src, dst)
     _check(lib.swz_copy_bytes(src.data_ptr(), dst.data_ptr(), nbytes, _stream_handle(stream)), "swz_copy_bytes")
 
 
@@ -205,6 +218,7 @@ def transpose(x, out=None, tile: int = 128, mode: int = MODE_XCD_GROUPM, stream=
     if out is None:
         out = torch.empty((N, M), dtype=x.dtype, device=x.device)
     assert out.is_cuda and out.is_contiguous() and tuple(out.shape) == (N, M) and out.dtype == x.dtype
+    _same_current_device(stream, x, out)
     p = _params(**params)
     _check(lib.swz_transpose(x.data_ptr(), out.data_ptr(), M, N, 2, int(tile), int(mode), ctypes.byref(p),
                              _stream_handle(stream)), "swz_transpose")
@@ -223,6 +237,7 @@ def _row_args(x, out):
 def softmax(x, out=None, chunks: int = 1, mode: int = MODE_XCD, stream=None, **params):
     """Row softmax of a bf16 matrix on the GPU through swz_softmax; `chunks` workgroups per row."""
     out = _row_args(x, out)
+    _same_current_device(stream, x, out)
     p = _params(**params)
     _check(lib.swz_softmax(x.data_ptr(), out.data_ptr(), x.shape[0], x.shape[1], int(chunks), int(mode), ctypes.byref(p),
                            _stream_handle(stream)), "swz_softmax")
@@ -234,6 +249,7 @@ def layernorm(x, gamma, beta, out=None, eps: float = 1e-5, chunks: int = 1, mode
     out = _row_args(x, out)
     for t in (gamma, beta):
         assert t.is_cuda and t.is_contiguous() and t.dtype == x.dtype and t.numel() == x.shape[1]
+    _same_current_device(stream, x, out, gamma, beta)
     p = _params(**params)
     _check(lib.swz_layernorm(x.data_ptr(), gamma.data_ptr(), beta.data_ptr(), out.data_ptr(), x.shape[0], x.shape[1],
                              float(eps), int(chunks), int(mode), ctypes.byref(p), _stream_handle(stream)), "swz_layernorm")
@@ -244,6 +260,7 @@ def mfma_peak(out, iters: int, random_operands: bool = True, stream=None) -> int
     """Launch the MFMA-rate measurement kernel (swz_mfma_peak); returns the flop count of the launch."""
     import torch
     assert out.is_cuda and out.is_contiguous() and out.dtype == torch.float32
+    _same_current_device(stream, out)
     wgs = ctypes.c_int(0)
     _check(lib.swz_mfma_peak(out.data_ptr(), out.numel(), int(iters), int(bool(random_operands)), ctypes.byref(wgs),
                              _stream_handle(stream)), "swz_mfma_peak")

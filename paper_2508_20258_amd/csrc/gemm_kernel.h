@@ -74,8 +74,6 @@
 #include <type_traits>
 #include <utility>
 
-#include <type_traits>
-
 #include "pid_decode.h"
 
 namespace swz {
@@ -156,26 +154,29 @@ __device__ __forceinline__ void wait_vmcnt() {
 // Written as inline assembly on purpose: the compiler then keeps no book on these loads, so it
 // does not guard later LDS reads of *other* ring slots with a conservative vmcnt(0); the kernel
 // waits for them itself (s_waitcnt vmcnt before the barrier that publishes a slot).
+// M0 is written by the scalar unit right before the load that reads it: on this generation such a
+// write needs one wait state before an LDS-DMA instruction uses it, and the compiler inserts wait
+// states only between instructions it emits itself, hence the s_nop inside the asm block.
 __device__ __forceinline__ void load_to_lds(const void* gptr, uint32_t lds_base) {
   const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(lds_base);   // wave-uniform by construction
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory", "m0");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory", "m0");
 }
 
 // Same, with the source given as a wave-uniform base (SGPR pair) plus a 32-bit per-lane byte offset.
 __device__ __forceinline__ void load_to_lds_base_off(const void* base, uint32_t off, uint32_t lds_base) {
   const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(lds_base);
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(off), "s"(base) : "memory", "m0");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(off), "s"(base) : "memory", "m0");
 }
 
-// One BM x BN tile of C, tile row pm, tile column pn, by the whole workgroup.  On return every
-// wave has issued its stores; LDS may still be read by slower waves (callers that reuse it put a
-// barrier first).
 // f(integral_constant<int, 0>{}), f(integral_constant<int, 1>{}), ... in order.
 template <class F, int... Is>
 __device__ __forceinline__ void for_each_index(F&& f, std::integer_sequence<int, Is...>) {
   (f(std::integral_constant<int, Is>{}), ...);
 }
 
+// One BM x BN tile of C, tile row pm, tile column pn, by the whole workgroup.  On return every
+// wave has issued its stores; LDS may still be read by slower waves (callers that reuse it put a
+// barrier first).
 template <class S>
 __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
                                           uint16_t* __restrict__ C, int M, int N, int K, int pm, int pn,

@@ -3,7 +3,12 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <stdlib.h>
+
+#include <atomic>
 #include <mutex>
+#include <tuple>
+#include <utility>
 
 #include "../../include/swz.h"
 #include "gemm_kernel.h"
@@ -20,11 +25,24 @@ constexpr int kDefaultBK = 64;  // K panel of a tile step; the kernel moves it a
 
 struct DeviceFacts {
   bool known = false;
-  int num_xcd = 0, cus = 0, l2_bytes = 0, lds_bytes = 0;
+  int num_xcd = 0, cus = 0, l2_bytes = 0, lds_bytes = 0;   // num_xcd 0: could not be derived
 };
 DeviceFacts g_facts[kMaxDevices];
-bool g_attr_set[kMaxDevices][2][4][2];
+std::atomic<bool> g_attr_set[kMaxDevices][2][4][2];
 std::mutex g_mu;
+
+// SWZ_NUM_XCD in the environment (read once per process): the XCD count to assume instead of the
+// one derived from the CU count, for partitioned devices.  0 = not set or not a number in 1..1024.
+int env_num_xcd() {
+  static const int value = [] {
+    const char* e = getenv("SWZ_NUM_XCD");
+    if (e == nullptr || *e == 0) return 0;
+    char* end = nullptr;
+    const long v = strtol(e, &end, 10);
+    return (end != nullptr && *end == 0 && v >= 1 && v <= 1024) ? (int)v : 0;
+  }();
+  return value;
+}
 
 int query_device(DeviceFacts* out) {
   int dev = 0;
@@ -39,12 +57,30 @@ int query_device(DeviceFacts* out) {
     f.cus = cus;
     f.l2_bytes = l2;
     f.lds_bytes = lds;
-    // A partitioned device exposes fewer CUs; XCDs always come in whole units of 32 CUs.
-    f.num_xcd = cus >= kCusPerXcd ? cus / kCusPerXcd : 1;
+    // XCDs come in whole units of 32 CUs (a partitioned device exposes fewer of them); any other
+    // CU count is not guessed at: the caller then has to name the XCD count.
+    if (env_num_xcd() > 0) f.num_xcd = env_num_xcd();
+    else f.num_xcd = (cus >= kCusPerXcd && cus % kCusPerXcd == 0) ? cus / kCusPerXcd : 0;
     f.known = true;
   }
   *out = f;
   return SWZ_OK;
+}
+
+// Launch through the call that returns the launch's own status: hipGetLastError() after a launch
+// would also report (and clear) an error some earlier, unrelated HIP call left behind.
+template <class... KArgs, size_t... Is>
+int launch_impl(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
+                std::tuple<KArgs...>& vals, std::index_sequence<Is...>) {
+  void* ptrs[] = {static_cast<void*>(&std::get<Is>(vals))...};
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds, stream) == hipSuccess ? SWZ_OK
+                                                                                                             : SWZ_ERR_HIP;
+}
+template <class... KArgs, class... Args>
+int launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t stream, Args... args) {
+  static_assert(sizeof...(KArgs) == sizeof...(Args), "argument count");
+  std::tuple<KArgs...> vals{static_cast<KArgs>(args)...};
+  return launch_impl(kernel, grid, block, lds, stream, vals, std::index_sequence_for<KArgs...>{});
 }
 
 bool valid_mode(int mode) { return mode >= SWZ_MODE_RR && mode <= SWZ_MODE_GROUPM; }
@@ -65,20 +101,17 @@ int launch_gemm_mode(const void* A, const void* B, void* C, int M, int N, int K,
   const int style = num_wg > 0 ? 1 : 0;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SWZ_ERR_HIP;
-  {
+  std::atomic<bool>& ready = g_attr_set[dev][slot][MODE][style];
+  if (!ready.load(std::memory_order_acquire)) {       // first launch of this kernel on this device only
     std::lock_guard<std::mutex> lock(g_mu);
-    if (!g_attr_set[dev][slot][MODE][style]) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              S::LDS_BYTES) != hipSuccess)
-        return SWZ_ERR_HIP;
-      g_attr_set[dev][slot][MODE][style] = true;
-    }
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            S::LDS_BYTES) != hipSuccess)
+      return SWZ_ERR_HIP;
+    ready.store(true, std::memory_order_release);
   }
   const unsigned blocks = (unsigned)(num_wg > 0 ? num_wg : grid_m * grid_n);
-  hipLaunchKernelGGL(kernel, dim3(blocks), dim3(S::NT), S::LDS_BYTES, stream,
-                     static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(B), static_cast<uint16_t*>(C),
-                     M, N, K, grid_m, grid_n, num_xcd, group_m);
-  return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
+  return launch(kernel, dim3(blocks), dim3(S::NT), S::LDS_BYTES, stream, static_cast<const uint16_t*>(A),
+                static_cast<const uint16_t*>(B), static_cast<uint16_t*>(C), M, N, K, grid_m, grid_n, num_xcd, group_m);
 }
 
 template <class S>
@@ -115,6 +148,7 @@ int resolve_plan(int64_t M, int64_t N, int64_t K, const swz_params* p, swz_param
     const int st = query_device(&f);
     if (st != SWZ_OK) return st;
     if (q.num_xcd == 0) q.num_xcd = f.num_xcd;
+    if (q.num_xcd == 0) return SWZ_ERR_UNSUPPORTED;   // CU count is not a whole number of XCDs: the caller must name it
     if (q.persistent && q.num_wg == 0) q.num_wg = f.cus;
   }
   if (!q.persistent) q.num_wg = 0;
@@ -132,13 +166,12 @@ int launch_transpose(const void* in, void* out, int M, int N, int gm, int gn, in
   auto* i = static_cast<const uint16_t*>(in);
   auto* o = static_cast<uint16_t*>(out);
   switch (mode) {
-    case SWZ_MODE_RR: hipLaunchKernelGGL((swz::transpose16_kernel<TILE, kModeRR>), grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m); break;
-    case SWZ_MODE_XCD: hipLaunchKernelGGL((swz::transpose16_kernel<TILE, kModeXcd>), grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m); break;
-    case SWZ_MODE_XCD_GROUPM: hipLaunchKernelGGL((swz::transpose16_kernel<TILE, kModeXcdGroupM>), grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m); break;
-    case SWZ_MODE_GROUPM: hipLaunchKernelGGL((swz::transpose16_kernel<TILE, kModeGroupM>), grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m); break;
+    case SWZ_MODE_RR: return launch(swz::transpose16_kernel<TILE, kModeRR>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m);
+    case SWZ_MODE_XCD: return launch(swz::transpose16_kernel<TILE, kModeXcd>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m);
+    case SWZ_MODE_XCD_GROUPM: return launch(swz::transpose16_kernel<TILE, kModeXcdGroupM>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m);
+    case SWZ_MODE_GROUPM: return launch(swz::transpose16_kernel<TILE, kModeGroupM>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m);
     default: return SWZ_ERR_INVALID_ARG;
   }
-  return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
 }
 // How the two row-wise entry points launch: threads per row (256, or 64 = one row per wave when a
 // single workgroup per row is asked for and the row has at most 2048 elements), 16-byte vectors a
@@ -166,6 +199,7 @@ int resolve_rows(int64_t M, int64_t N, int chunks, int mode, const swz_params* p
     const int st = query_device(&f);
     if (st != SWZ_OK) return st;
     plan->num_xcd = f.num_xcd;
+    if (plan->num_xcd == 0) return SWZ_ERR_UNSUPPORTED;
   }
   plan->chunk_vecs = (int)((nv + chunks - 1) / chunks);
   plan->tpr = (chunks == 1 && nv <= 4 * 64) ? 64 : swz::kRowThreads;
@@ -176,13 +210,13 @@ int resolve_rows(int64_t M, int64_t N, int chunks, int mode, const swz_params* p
   return check_map_args(plan->grid_m, chunks, plan->num_xcd, &plan->group_m, mode);
 }
 
-#define SWZ_LAUNCH_BY_MODE(KERNEL, KEEP, TPR, ...)                                                                       \
-  switch (mode) {                                                                                                        \
-    case SWZ_MODE_RR: hipLaunchKernelGGL((KERNEL<kModeRR, KEEP, TPR>), grid, block, 0, stream, __VA_ARGS__); break;       \
-    case SWZ_MODE_XCD: hipLaunchKernelGGL((KERNEL<kModeXcd, KEEP, TPR>), grid, block, 0, stream, __VA_ARGS__); break;     \
-    case SWZ_MODE_XCD_GROUPM: hipLaunchKernelGGL((KERNEL<kModeXcdGroupM, KEEP, TPR>), grid, block, 0, stream, __VA_ARGS__); break; \
-    case SWZ_MODE_GROUPM: hipLaunchKernelGGL((KERNEL<kModeGroupM, KEEP, TPR>), grid, block, 0, stream, __VA_ARGS__); break; \
-    default: return SWZ_ERR_INVALID_ARG;                                                                                 \
+#define SWZ_LAUNCH_BY_MODE(KERNEL, KEEP, TPR, ...)                                                                \
+  switch (mode) {                                                                                                 \
+    case SWZ_MODE_RR: return launch(KERNEL<kModeRR, KEEP, TPR>, grid, block, 0, stream, __VA_ARGS__);             \
+    case SWZ_MODE_XCD: return launch(KERNEL<kModeXcd, KEEP, TPR>, grid, block, 0, stream, __VA_ARGS__);           \
+    case SWZ_MODE_XCD_GROUPM: return launch(KERNEL<kModeXcdGroupM, KEEP, TPR>, grid, block, 0, stream, __VA_ARGS__); \
+    case SWZ_MODE_GROUPM: return launch(KERNEL<kModeGroupM, KEEP, TPR>, grid, block, 0, stream, __VA_ARGS__);     \
+    default: return SWZ_ERR_INVALID_ARG;                                                                          \
   }
 #define SWZ_LAUNCH_BY_PLAN(KERNEL, ...)                                          \
   if (plan.tpr == 64) {                                                          \
@@ -238,9 +272,8 @@ int swz_pid_map_device(int grid_m, int grid_n, int num_xcd, int group_m, int mod
   if (d_tile == nullptr) return SWZ_ERR_INVALID_ARG;
   const int st = check_map_args(grid_m, grid_n, num_xcd, &group_m, mode);
   if (st != SWZ_OK) return st;
-  hipLaunchKernelGGL(swz::pid_map_kernel, dim3((unsigned)(grid_m * grid_n)), dim3(64), 0, stream, grid_m, grid_n,
-                     num_xcd, group_m, mode, d_tile, d_xcc);
-  return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
+  return launch(swz::pid_map_kernel, dim3((unsigned)(grid_m * grid_n)), dim3(64), 0, stream, grid_m, grid_n, num_xcd,
+                group_m, mode, d_tile, d_xcc);
 }
 
 int swz_pid_map_persistent(int grid_m, int grid_n, int num_xcd, int group_m, int mode, int num_wg, int32_t* out) {
@@ -272,9 +305,8 @@ int swz_pid_map_persistent_device(int grid_m, int grid_n, int num_xcd, int group
   if (st != SWZ_OK) return st;
   const int64_t rounds = ((int64_t)grid_m * grid_n + num_wg - 1) / num_wg;
   if (rounds * num_wg >= (int64_t)1 << 31) return SWZ_ERR_OVERFLOW;
-  hipLaunchKernelGGL(swz::pid_map_persistent_kernel, dim3((unsigned)num_wg), dim3(64), 0, stream, grid_m, grid_n,
-                     num_xcd, group_m, mode, (int)rounds, d_tile, d_xcc);
-  return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
+  return launch(swz::pid_map_persistent_kernel, dim3((unsigned)num_wg), dim3(64), 0, stream, grid_m, grid_n, num_xcd,
+                group_m, mode, (int)rounds, d_tile, d_xcc);
 }
 
 int swz_transpose(const void* in, void* out, int64_t M, int64_t N, int elem_bytes, int tile, int mode,
@@ -295,6 +327,7 @@ int swz_transpose(const void* in, void* out, int64_t M, int64_t N, int elem_byte
     const int st = query_device(&f);
     if (st != SWZ_OK) return st;
     num_xcd = f.num_xcd;
+    if (num_xcd == 0) return SWZ_ERR_UNSUPPORTED;
   }
   const int64_t gm = (M + tile - 1) / tile, gn = (N + tile - 1) / tile;
   if (gm * gn >= lim) return SWZ_ERR_OVERFLOW;
@@ -315,7 +348,6 @@ int swz_softmax(const void* in, void* out, int64_t M, int64_t N, int chunks, int
   const dim3 grid((unsigned)((int64_t)plan.grid_m * chunks)), block(swz::kRowThreads);
   SWZ_LAUNCH_BY_PLAN(swz::softmax_rows_kernel, static_cast<const uint16_t*>(in), static_cast<uint16_t*>(out), (int)M,
                      (int)N, chunks, plan.chunk_vecs, plan.num_xcd, plan.group_m)
-  return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
 }
 
 int swz_layernorm(const void* in, const void* gamma, const void* beta, void* out, int64_t M, int64_t N, float eps,
@@ -331,7 +363,6 @@ int swz_layernorm(const void* in, const void* gamma, const void* beta, void* out
   SWZ_LAUNCH_BY_PLAN(swz::layernorm_rows_kernel, static_cast<const uint16_t*>(in), static_cast<const uint16_t*>(gamma),
                      static_cast<const uint16_t*>(beta), static_cast<uint16_t*>(out), (int)M, (int)N, eps, chunks,
                      plan.chunk_vecs, plan.num_xcd, plan.group_m)
-  return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
 }
 
 int swz_mfma_peak(float* out, int64_t out_floats, int iters, int random_operands, int* workgroups, hipStream_t stream) {
@@ -341,8 +372,7 @@ int swz_mfma_peak(float* out, int64_t out_floats, int iters, int random_operands
   if (st != SWZ_OK) return st;
   if (out_floats < (int64_t)f.cus * 512) return SWZ_ERR_INVALID_ARG;
   if (workgroups != nullptr) *workgroups = f.cus;
-  hipLaunchKernelGGL(swz::mfma_peak_kernel, dim3((unsigned)f.cus), dim3(512), 0, stream, out, iters, random_operands ? 1 : 0);
-  return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
+  return launch(swz::mfma_peak_kernel, dim3((unsigned)f.cus), dim3(512), 0, stream, out, iters, random_operands ? 1 : 0);
 }
 
 int swz_copy_bytes(const void* src, void* dst, int64_t bytes, hipStream_t stream) {
@@ -351,9 +381,8 @@ int swz_copy_bytes(const void* src, void* dst, int64_t bytes, hipStream_t stream
   const int64_t n = bytes / 16;
   const int64_t want = (n + 255) / 256;
   const unsigned blocks = (unsigned)(want < 8192 ? want : 8192);
-  hipLaunchKernelGGL(swz::copy16_kernel, dim3(blocks), dim3(256), 0, stream, static_cast<const swz::u32x4*>(src),
-                     static_cast<swz::u32x4*>(dst), n);
-  return hipGetLastError() == hipSuccess ? SWZ_OK : SWZ_ERR_HIP;
+  return launch(swz::copy16_kernel, dim3(blocks), dim3(256), 0, stream, static_cast<const swz::u32x4*>(src),
+                static_cast<swz::u32x4*>(dst), n);
 }
 
 int swz_gemm_plan(int64_t M, int64_t N, int64_t K, const swz_params* params, swz_params* resolved, int* grid_m,

@@ -147,3 +147,19 @@ def test_build_script_runs_without_importing_the_package():
     assert mod.build(force=False) == swz.binding.LIB_PATH          # up to date: returns without compiling
     entry = open(os.path.join(ROOT, "__graft_entry__.py")).read()
     assert "from paper_2508_20258_amd.build import" not in entry
+
+
+def test_binding_refuses_tensors_of_another_device(monkeypatch):
+    # the library launches on the current device; a tensor living elsewhere must be caught before the call
+    import types
+
+    import torch
+    monkeypatch.setattr(torch.cuda, "current_device", lambda: 0)
+    here = types.SimpleNamespace(device=types.SimpleNamespace(index=0))
+    there = types.SimpleNamespace(device=types.SimpleNamespace(index=1))
+    swz.binding._same_current_device(None, here, here)
+    with pytest.raises(ValueError):
+        swz.binding._same_current_device(None, here, there)
+    with pytest.raises(ValueError):
+        swz.binding._same_current_device(there, here)
+    swz.binding._same_current_device(here, here)
