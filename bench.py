@@ -5,13 +5,16 @@ decode, global->LDS staging, MFMA loop, epilogue) over the 4096^3 workload, inpu
 in HBM.  Prints ONE JSON line.  `value` is the throughput of the swizzled mapping (XCD
 renumbering + grouped-M raster) over exactly --steps timed launches; the round-robin and
 XCD-only mappings and the persistent launch style, timed interleaved in the same run, are
-reported beside it, as are the 8192^3 and the skinny 16384x2048x8192 workloads and, under
-"other_kernels", the transpose / softmax / layer normalisation kernels (HBM-bound; not part of `value`).
+reported beside it ("modes"), and the same comparison for the other four workloads
+("other_workloads": 512^3, 8192^3, the skinny 16384x2048x8192 and the ragged 10000x7000x4096).
+L2 hit rates (total and per XCD) and HBM/fabric bytes cannot be read inside this process: they
+are the rocprofv3 counters `harness profile --record` stored for exactly these kernel sources
+(null when the sources have changed since).  Under "other_kernels": the transpose / softmax /
+layer normalisation kernels (HBM-bound; not part of `value`).
 """
 from __future__ import annotations
 
 import argparse
-import hashlib
 import json
 import os
 import sys
@@ -23,24 +26,23 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA, published (256 CUs x 4 SIMDs x 1024 flop/clk x 2.4 GHz)
 
-# HBM/fabric bytes per launch of the swizzled kernel from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE (KiB per dispatch), each scaled by what the same counter reads for the library's
-# plain 1 GiB copy kernel (FETCH_SIZE reads 0.5x the bytes copied, WRITE_SIZE 1.0x).  Valid only
-# for the kernel source whose hash is recorded here; any other kernel reports null.
-TRAFFIC = {
-    "kernel_sha256": "0ce3389157eaf6ae8f5b930bdd7d46dddd251af9b7fd3683d0890debdb670dcf",
-    # FETCH_SIZE 98421 KiB x 2.000 + WRITE_SIZE 32786 KiB x 1.000 per dispatch (profiles/gemm_cfg2_4096.txt)
-    "cfg2_4096": {"xcd_groupm": {"fetch_bytes": 201565312, "write_bytes": 33572650, "total_bytes": 235137962,
-                                 "algorithmic_min_bytes": 100663296}},
-}
+PER_PASS = 20                    # launches per timing sample of the mapping comparison, whatever --steps is
 
 
-def kernel_hash() -> str:
-    h = hashlib.sha256()
-    for name in ("gemm_kernel.h", "pid_decode.h"):
-        with open(os.path.join(ROOT, "paper_2508_20258_amd", "csrc", name), "rb") as f:
-            h.update(f.read())
-    return h.hexdigest()
+def recorded(workload):
+    """rocprofv3 counters stored for this workload and the kernel sources as they are now (else None):
+    per mapping, L2 hit rate (TCC_HIT/(TCC_HIT+TCC_MISS), total and per XCD) and HBM/fabric bytes per launch
+    (FETCH_SIZE, WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for the
+    library's plain 1 GiB copy kernel)."""
+    from paper_2508_20258_amd import harness
+    return harness.recorded_counters(workload)
+
+
+def l2_hit_rates(rec):
+    if not rec:
+        return None
+    return {mode: {"total": r["l2_hit_pct"], "per_xcd": r["l2_hit_pct_per_xcd"], "panel_model": r["model_hit_pct"]}
+            for mode, r in rec.items()}
 
 
 def time_mode(swz, torch, a, b, c, mode, steps, warmup, **params):
@@ -114,22 +116,31 @@ def measured_mfma_peak(swz, torch):
 
 def other_kernels(swz, torch):
     """The paper's other kernels built here (transpose, row softmax, layer normalisation): round-robin against the
-    remapped program ids, GB/s of the algorithmic 4*M*N bytes against the 8 TB/s HBM roofline."""
+    remapped program ids, GB/s of the algorithmic 4*M*N bytes against the 8 TB/s HBM roofline, and against the rate
+    the library's plain copy kernel reaches in this same run on the same amount of data."""
     res = {}
 
-    def entry(us, m, n):
+    def entry(us, m, n, copy_gbs=None):
         gbs = 4.0 * m * n / (us * 1e-6) / 1e9
-        return dict(us=us, gb_per_s=gbs, frac_hbm_peak=gbs / 8000.0)
+        e = dict(us=us, gb_per_s=gbs, frac_hbm_peak=gbs / 8000.0)
+        if copy_gbs:
+            e["frac_of_plain_copy"] = gbs / copy_gbs
+        return e
 
     m = n = 16384
     x = torch.randint(-32768, 32767, (m, n), dtype=torch.int16, device="cuda").view(torch.bfloat16)
     y = torch.empty((n, m), dtype=torch.bfloat16, device="cuda")
+    us = time_calls(torch, lambda: swz.copy_bytes(x, y))
+    copy_gbs = 4.0 * m * n / (us * 1e-6) / 1e9
+    res[f"plain_copy_{m}x{n}"] = entry(us, m, n)
     for tile in (128, 64, 32):
         for mode in ("rr", "xcd_groupm"):
             us = time_calls(torch, lambda: swz.transpose(x, y, tile=tile, mode=swz.MODES[mode]))
-            res[f"transpose_{m}x{n}_tile{tile}_{mode}"] = entry(us, m, n)
+            res[f"transpose_{m}x{n}_tile{tile}_{mode}"] = entry(us, m, n, copy_gbs)
     del x, y
-    for (m, n, chunks) in ((1024, 65536, 8), (8192, 8192, 1)):
+    # 32768 x 16384: 1 GiB in, 1 GiB out, beyond what the 256 MB memory-side cache can hold between launches;
+    # the smaller cases are partly served from it and are listed for the mapping comparison only
+    for (m, n, chunks) in ((32768, 16384, 1), (1024, 65536, 8), (8192, 8192, 1)):
         x = (torch.randn((m, n), device="cuda") * 2.0).to(torch.bfloat16)
         y = torch.empty_like(x)
         g = torch.rand(n, device="cuda").to(torch.bfloat16)
@@ -196,15 +207,19 @@ def main():
     variants = [("rr", {}), ("xcd", {}), ("xcd_groupm", {}),
                 # the paper's own launch style (as many workgroups as compute units, tile loop)
                 ("persistent_rr", dict(persistent=1)), ("persistent_xcd_groupm", dict(persistent=1))]
-    per_mode = compare_mappings(swz, torch, a, b, c, variants, max(args.steps // 10, 1), args.warmup, flops)
+    per_mode = compare_mappings(swz, torch, a, b, c, variants, PER_PASS, max(args.warmup, PER_PASS), flops)
     # the headline run: exactly `steps` timed launches of the swizzled kernel
     ms, wall_ms = time_mode(swz, torch, a, b, c, swz.MODE_XCD_GROUPM, args.steps, args.warmup)
     tflops = flops / ms / 1e9
 
+    rec = recorded(args.workload)
     traffic, traffic_detail = None, None
-    rec = TRAFFIC.get(args.workload, {}).get("xcd_groupm")
-    if rec is not None and TRAFFIC["kernel_sha256"] == kernel_hash():
-        traffic, traffic_detail = rec["total_bytes"], rec
+    if rec and "xcd_groupm" in rec:
+        r = rec["xcd_groupm"]
+        traffic = r["fetch_bytes"] + r["write_bytes"]
+        traffic_detail = {"fetch_bytes": r["fetch_bytes"], "write_bytes": r["write_bytes"], "total_bytes": traffic,
+                          "algorithmic_min_bytes": 2 * (M * K + K * N + M * N),
+                          "fetch_bytes_by_mode": {m: v["fetch_bytes"] for m, v in rec.items()}}
 
     out = {
         "metric": "bf16 GEMM TFLOP/s + % MFMA peak + L2 hit rate, swizzled vs round-robin PID",
@@ -218,7 +233,9 @@ def main():
         "wall_ms_per_step": wall_ms,
         "modes": per_mode,
         "swizzled_over_rr": per_mode["xcd_groupm"]["tflops"] / per_mode["rr"]["tflops"],
-        "l2_hit_rate": "not measurable inside this process; rocprofv3 TCC_HIT/TCC_MISS summaries per workload and mode are under profiles/",
+        "l2_hit_rate": l2_hit_rates(rec),
+        "l2_hit_rate_source": "rocprofv3 --pmc TCC_HIT TCC_MISS on this kernel source (harness profile --record); percent; "
+                              "null when the kernel sources differ from the profiled ones",
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": tflops / PEAK_BF16_TFLOPS, "traffic": traffic},
         "traffic_detail": traffic_detail,
@@ -236,16 +253,20 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         out["context_vendor_blas_tflops"] = flops / (e0.elapsed_time(e1) / 50) / 1e9
-        # the large square workload and the skinny projection-shaped one (where the default dispatch
-        # hurts most), same launch path, same interleaved comparison
+        # the other four workloads (small, large square, skinny projection-shaped, ragged), same launch path,
+        # same interleaved comparison; launches per sample sized so that a sample lasts a few milliseconds
         out["other_workloads"] = {}
-        for other in ("cfg3_8192", "cfg4_skinny"):
+        for other in [w for w in si.CONFIGS if w != args.workload]:
             oc = si.CONFIGS[other]
             ab, bb = si.config_inputs(other)
             a3, b3 = to_device(torch, np, ab), to_device(torch, np, bb)
             c3 = torch.empty((oc["M"], oc["N"]), dtype=torch.bfloat16, device="cuda")
             f3 = 2.0 * oc["M"] * oc["N"] * oc["K"]
-            out["other_workloads"][other] = compare_mappings(swz, torch, a3, b3, c3, variants, 8, 4, f3)
+            n3 = 200 if f3 < 1e10 else PER_PASS if f3 < 2e11 else 8
+            res = compare_mappings(swz, torch, a3, b3, c3, variants, n3, n3, f3)
+            res["l2_hit_rate"] = l2_hit_rates(recorded(other))
+            res["swizzled_over_rr"] = res["xcd_groupm"]["tflops"] / res["rr"]["tflops"]
+            out["other_workloads"][other] = res
             del a3, b3, c3, ab, bb
 
     if not args.no_extras:

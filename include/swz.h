@@ -184,6 +184,23 @@ int swz_softmax(const void* in, void* out, int64_t M, int64_t N, int chunks, int
 int swz_layernorm(const void* in, const void* gamma, const void* beta, void* out, int64_t M, int64_t N, float eps,
                   int chunks, int mode, const swz_params* params, hipStream_t stream);
 
+/* Measurement aid: swz_gemm_ex (one workgroup per tile only; persistent = 1 is UNSUPPORTED) run by
+ * an instantiation of the same kernel that also takes time stamps, so that what bounds the kernel
+ * (clock under load, cycles per K step, when each XCD finishes) can be read per workgroup.  The
+ * stamps are kept in scalar registers while the tile is computed and written once at its end: the
+ * loop's instruction stream is the product kernel's.  C is computed as by swz_gemm_ex.
+ *   probe       : DEVICE buffer, 8-byte aligned, of probe_words >= 16 * grid_m * grid_n 64-bit words;
+ *                 workgroup w (hardware id) writes words 16w .. 16w+15:
+ *                 0,1  shader clock counter / constant 100 MHz counter at kernel entry
+ *                 2,3  the same pair when the K loop starts (first operands have landed)
+ *                 4,5  when the K loop has ended        6,7  when the last store has been issued
+ *                 8    XCC_ID (the XCD it ran on)       9    HW_ID register
+ *                 10   K steps of 32 the loop made      11, 12  tile row, tile column      13..15  zero
+ * Asynchronous on `stream`; never allocates or synchronises.  Errors as swz_gemm_ex, plus INVALID_ARG
+ * (null or too small probe buffer). */
+int swz_gemm_probe(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,
+                   const swz_params* params, uint64_t* probe, int64_t probe_words, hipStream_t stream);
+
 /* Measurement aid, not part of the GEMM path: a plain streaming copy of `bytes` bytes
  * (reads `bytes`, writes `bytes`; both DEVICE pointers 16-byte aligned, bytes a multiple of
  * 16, buffers must not overlap).  The profiling harness scales the profiler's HBM byte

@@ -7,5 +7,5 @@ the library's HIP kernels; this package only marshals arguments.  Importing it l
 from .binding import (  # noqa: F401
     MODE_GROUPM, MODE_RR, MODE_XCD, MODE_XCD_GROUPM, MODES, DTYPE_BF16, SwzError, SwzParams, copy_bytes, device_info, gemm,
     gemm_plan, lib, pid_map, pid_map_device, pid_map_persistent, pid_map_persistent_device, status_string, transpose,
-    layernorm, mfma_peak, softmax,
+    layernorm, mfma_peak, softmax, gemm_probe, PROBE_WORDS,
 )

@@ -18,7 +18,7 @@ DTYPE_BF16 = 0
 
 EXPORTS = ("swz_status_string", "swz_device_info", "swz_pid_map", "swz_pid_map_device", "swz_gemm", "swz_gemm_ex",
            "swz_gemm_plan", "swz_copy_bytes", "swz_pid_map_persistent", "swz_pid_map_persistent_device", "swz_transpose",
-           "swz_softmax", "swz_layernorm", "swz_mfma_peak")
+           "swz_softmax", "swz_layernorm", "swz_mfma_peak", "swz_gemm_probe")
 
 
 class SwzParams(ctypes.Structure):
@@ -67,6 +67,7 @@ def _load() -> ctypes.CDLL:
     L.swz_gemm.argtypes = [vp, vp, vp, i64, i64, i64, i, i, vp]
     L.swz_gemm_ex.argtypes = [vp, vp, vp, i64, i64, i64, i, i, pp, vp]
     L.swz_gemm_plan.argtypes = [i64, i64, i64, pp, pp, ip, ip]
+    L.swz_gemm_probe.argtypes = [vp, vp, vp, i64, i64, i64, i, i, pp, vp, i64, vp]
     L.swz_copy_bytes.argtypes = [vp, vp, i64, vp]
     L.swz_transpose.argtypes = [vp, vp, i64, i64, i, i, i, pp, vp]
     L.swz_softmax.argtypes = [vp, vp, i64, i64, i, i, pp, vp]
@@ -174,6 +175,31 @@ def gemm(a, b, c=None, mode: int = MODE_XCD_GROUPM, stream=None, **params):
     else:
         _check(lib.swz_gemm(a.data_ptr(), b.data_ptr(), c.data_ptr(), M, N, K, DTYPE_BF16, int(mode), h), "swz_gemm")
     return c
+
+
+PROBE_WORDS = 16
+
+
+def gemm_probe(a, b, c=None, mode: int = MODE_XCD_GROUPM, stream=None, **params):
+    """swz_gemm_probe: C = A @ B by the time-stamping instantiation of the kernel.
+
+    Returns (c, probe): probe is an int64 CUDA tensor of shape (workgroups, 16), row w written by hardware
+    workgroup w (layout in include/swz.h)."""
+    import torch
+    assert a.is_cuda and b.is_cuda and a.dtype == torch.bfloat16 and b.dtype == torch.bfloat16
+    assert a.is_contiguous() and b.is_contiguous() and a.dim() == 2 and b.dim() == 2 and a.shape[1] == b.shape[0]
+    M, K = a.shape
+    N = b.shape[1]
+    if c is None:
+        c = torch.empty((M, N), dtype=torch.bfloat16, device=a.device)
+    assert c.is_cuda and c.dtype == torch.bfloat16 and c.is_contiguous() and tuple(c.shape) == (M, N)
+    _same_current_device(stream, a, b, c)
+    plan = gemm_plan(M, N, K, **params)
+    probe = torch.full((plan["grid_m"] * plan["grid_n"], PROBE_WORDS), -1, dtype=torch.int64, device=a.device)
+    p = _params(**params)
+    _check(lib.swz_gemm_probe(a.data_ptr(), b.data_ptr(), c.data_ptr(), M, N, K, DTYPE_BF16, int(mode), ctypes.byref(p),
+                              probe.data_ptr(), probe.numel(), _stream_handle(stream)), "swz_gemm_probe")
+    return c, probe
 
 
 def copy_bytes(src, dst, stream=None) -> None:

@@ -55,9 +55,15 @@
 //     clocks of the other group's MFMAs and the MFMA pipe idled 10 % of the time.
 // Steps past the end of K are fetched as zeros, which keeps the loop free of tail cases.
 //
-// Epilogue.  Each wave converts its accumulators to bf16 (nearest even), writes them to a
-// wave-private LDS patch and reads them back row-wise, so that global stores are 16 bytes
-// per lane and cover whole 128-byte lines.
+// Epilogue.  Each wave converts its accumulators to bf16 (nearest even) and rearranges them across
+// lanes in registers (v_permlane16_swap between the registers of two neighbouring column blocks, then
+// a rotation by 8 inside each 16-lane row), so that every lane holds 16 contiguous bytes and one
+// store instruction covers whole 128-byte lines.  LDS is not involved, which lets a workgroup that
+// has another tile to compute (persistent launch) start that tile's first loads before it converts
+// and stores the current one.  Measured: neither the register epilogue (against a transposition
+// through LDS patches) nor the overlap changes the rate by more than the noise, 0.5 %: what the
+// chip delivers on this kernel is set by the power its arithmetic and its operand traffic draw, not
+// by the few microseconds at either end of a tile.
 //
 // LDS layouts (16-byte chunks, XOR-swizzled so that the read patterns spread over banks):
 //   A: row r at byte r*128, chunk c (8 k-values, c = 0..7 over the double) stored in slot
@@ -106,15 +112,10 @@ struct GemmShape {
   static constexpr int A_LOADS = BM * 8 / NT;      // 16-byte chunks each thread moves per A double
   static constexpr int B_LOADS = kStepK * B_ROW_CHUNKS / NT;   // ... per B step
   static constexpr int LOADS = A_LOADS / 2 + B_LOADS;          // loads each thread issues per step
-  // epilogue patch of one wave: (TM*16) rows of (TN*16) bf16, row pitch padded by 16 bytes
-  static constexpr int EPI_PITCH = TN * 16 * 2 + 16;
-  static constexpr int EPI_WAVE_BYTES = TM * 16 * EPI_PITCH;
-  static constexpr int EPI_BYTES = NW * EPI_WAVE_BYTES;
-  static constexpr int LDS_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
+  static constexpr int LDS_BYTES = RING_BYTES;
   static_assert(BM % (WM * 16) == 0 && BN % (WN * 16) == 0, "wave tiling");
   static_assert((BM * 8) % NT == 0 && (kStepK * B_ROW_CHUNKS) % NT == 0 && A_LOADS % 2 == 0, "load tiling");
   static_assert(A_LOADS / 2 == B_LOADS, "A and B loads alternate within a step");
-  static_assert(TN * 16 * 2 / 16 <= 64 && 64 % (TN * 16 * 2 / 16) == 0, "epilogue row must divide a wave");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS per workgroup");
 };
 
@@ -174,16 +175,38 @@ __device__ __forceinline__ void for_each_index(F&& f, std::integer_sequence<int,
   (f(std::integral_constant<int, Is>{}), ...);
 }
 
+// What the timing instantiation of the kernel records per workgroup (64-bit words): the shader clock
+// counter and the constant 100 MHz counter at kernel entry, at the start and at the end of the K
+// loop and after the last store was issued, then XCC_ID, HW_ID, the number of K steps, tile row,
+// tile column.
+constexpr int kProbeWords = 16;
+
 // One BM x BN tile of C, tile row pm, tile column pn, by the whole workgroup.  On return every
-// wave has issued its stores; LDS may still be read by slower waves (callers that reuse it put a
-// barrier first).
-template <class S>
+// wave has issued its stores and LDS is no longer read.
+//   staged   : the loads that open this tile's K loop (A doubles 0, 1, B steps 0..2) are already
+//              under way: the previous call was given this tile as its next one;
+//   has_next : another tile (npm, npn) follows in this workgroup: its opening loads are issued as
+//              soon as the K loop has let go of LDS, before the accumulators are converted and
+//              stored, so that their latency runs under the epilogue.
+//   PROBE    : timing instantiation, see kProbeWords (probe = this workgroup's 16 words); the
+//              stamps live in scalar registers until the tile is done, so the instruction stream
+//              of the loop and every counter wait in it are those of the product kernel.
+template <class S, bool PROBE = false>
 __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
                                           uint16_t* __restrict__ C, int M, int N, int K, int pm, int pn,
-                                          unsigned char* smem) {
+                                          bool staged, bool has_next, int npm, int npn, unsigned char* smem,
+                                          uint64_t* probe = nullptr) {
   constexpr int BM = S::BM, BN = S::BN, TM = S::TM, TN = S::TN;
   const int m0 = pm * BM;
   const int n0 = pn * BN;
+  uint64_t stamp[8];
+  auto take_stamp = [&](int i) __attribute__((always_inline)) {
+    if constexpr (PROBE) {
+      stamp[2 * i] = __builtin_readcyclecounter();
+      stamp[2 * i + 1] = __builtin_amdgcn_s_memrealtime();
+    }
+  };
+  take_stamp(0);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -194,26 +217,31 @@ __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const 
   // ---- global -> LDS staging: which chunk this lane fetches for each of its loads ----
   // A load i (0 .. A_LOADS-1) of wave w fills LDS bytes [(w*A_LOADS + i)*1024, +1024) of an A slot:
   // 8 rows x 128 bytes.  B load i fills [(w*B_LOADS + i)*1024, +1024) of a B slot: 2 rows x 512 bytes.
-  // A lane's source is  tile base (uniform, advances with k) + a 32-bit byte offset that never changes.
+  // A lane's source is  tile base (uniform, advances with k) + a 32-bit byte offset that never changes
+  // while a tile is being computed.
   uint32_t a_off[S::A_LOADS], b_off[S::B_LOADS];
+  const unsigned char *a_tile, *b_tile;
+  auto aim_at = [&](int tm0, int tn0) __attribute__((always_inline)) {
 #pragma unroll
-  for (int i = 0; i < S::A_LOADS; ++i) {
-    const int q = (wave * S::A_LOADS + i) * 64 + lane;
-    const int row = q >> 3, slot = q & 7;
-    const int c = a_slot(row, slot);           // XOR with a key is its own inverse
-    const int r = (m0 + row < M) ? row : (M - 1 - m0);
-    a_off[i] = (uint32_t)r * (uint32_t)K * 2u + (uint32_t)c * 16u;
-  }
+    for (int i = 0; i < S::A_LOADS; ++i) {
+      const int q = (wave * S::A_LOADS + i) * 64 + lane;
+      const int row = q >> 3, slot = q & 7;
+      const int c = a_slot(row, slot);           // XOR with a key is its own inverse
+      const int r = (tm0 + row < M) ? row : (M - 1 - tm0);
+      a_off[i] = (uint32_t)r * (uint32_t)K * 2u + (uint32_t)c * 16u;
+    }
 #pragma unroll
-  for (int i = 0; i < S::B_LOADS; ++i) {
-    const int q = (wave * S::B_LOADS + i) * 64 + lane;
-    const int krow = q / S::B_ROW_CHUNKS, slot = q % S::B_ROW_CHUNKS;
-    const int c = slot ^ b_key(krow);
-    const int col = (n0 + c * 8 < N) ? c * 8 : (N - 8 - n0);
-    b_off[i] = (uint32_t)krow * (uint32_t)N * 2u + (uint32_t)col * 2u;
-  }
-  const unsigned char* a_tile = reinterpret_cast<const unsigned char*>(A + (size_t)m0 * K);
-  const unsigned char* b_tile = reinterpret_cast<const unsigned char*>(B + n0);
+    for (int i = 0; i < S::B_LOADS; ++i) {
+      const int q = (wave * S::B_LOADS + i) * 64 + lane;
+      const int krow = q / S::B_ROW_CHUNKS, slot = q % S::B_ROW_CHUNKS;
+      const int c = slot ^ b_key(krow);
+      const int col = (tn0 + c * 8 < N) ? c * 8 : (N - 8 - tn0);
+      b_off[i] = (uint32_t)krow * (uint32_t)N * 2u + (uint32_t)col * 2u;
+    }
+    a_tile = reinterpret_cast<const unsigned char*>(A + (size_t)tm0 * K);
+    b_tile = reinterpret_cast<const unsigned char*>(B + tn0);
+  };
+  aim_at(m0, n0);
   const size_t a_dbl = (size_t)2 * kStepK * 2;        // bytes per A double along a row of A
   const size_t b_step = (size_t)kStepK * N * 2;       // bytes per K step down the rows of B
   const unsigned char* zero = reinterpret_cast<const unsigned char*>(&kZeroChunk);
@@ -359,20 +387,30 @@ __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const 
   };
 
   const int KT = (K + kStepK - 1) / kStepK;
-  // prologue: A doubles 0 and 1, B steps 0 .. 2 (what MEM(0) and MEM(1) do not fetch themselves)
-  static_assert(kBSlots == 4 && kASlots == 3, "prologue order is written for these ring depths");
+  // the loads that open a tile: A doubles 0 and 1, B steps 0 .. 2 (what MEM(0) and MEM(1) do not fetch themselves)
+  static_assert(kBSlots == 4 && kASlots == 3, "the opening order is written for these ring depths");
+  auto open_tile = [&]() __attribute__((always_inline)) {
 #pragma unroll
-  for (int i = 0; i < S::A_LOADS; ++i) load_a(0, 0, i, kTail);
+    for (int i = 0; i < S::A_LOADS; ++i) load_a(0, 0, i, kTail);
 #pragma unroll
-  for (int i = 0; i < S::B_LOADS; ++i) load_b(0, 0, i, kTail);
+    for (int i = 0; i < S::B_LOADS; ++i) load_b(0, 0, i, kTail);
 #pragma unroll
-  for (int i = 0; i < S::B_LOADS; ++i) load_b(1, 1, i, kTail);
+    for (int i = 0; i < S::B_LOADS; ++i) load_b(1, 1, i, kTail);
 #pragma unroll
-  for (int i = 0; i < S::A_LOADS; ++i) load_a(1, 1, i, kTail);
+    for (int i = 0; i < S::A_LOADS; ++i) load_a(1, 1, i, kTail);
 #pragma unroll
-  for (int i = 0; i < S::B_LOADS; ++i) load_b(2, 2, i, kTail);
-  wait_vmcnt<S::A_LOADS + (kBSlots - 2) * S::B_LOADS>();          // A double 0 and B step 0 have landed (this wave's part)
+    for (int i = 0; i < S::B_LOADS; ++i) load_b(2, 2, i, kTail);
+  };
+  if (!staged) {
+    open_tile();
+    wait_vmcnt<S::A_LOADS + (kBSlots - 2) * S::B_LOADS>();        // A double 0 and B step 0 have landed (this wave's part)
+  } else {
+    // issued during the previous tile's epilogue, whose stores share the counter and may complete out of
+    // order with loads: wait for everything
+    wait_vmcnt<0>();
+  }
   __syncthreads();                                               // ... and everybody else's
+  take_stamp(1);
   if (grp == 1) phase_barrier();                                 // group 1 starts one phase later
 
   // one step whose position in the slot cycle (B: 4 steps, A: 3 doubles = 6 steps, together 12)
@@ -406,34 +444,83 @@ __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const 
   for (; t < KT; t += 2) step_pair(t, kTail);
   if (grp == 0) phase_barrier();                                 // group 1's last compute phase
 
-  // ---- epilogue: fp32 -> bf16 (nearest even), transpose through a wave-private LDS patch ----
+  // ---- epilogue: fp32 -> bf16 (nearest even), rearranged across lanes in registers, 16-byte stores ----
   wait_vmcnt<0>();   // the zero-filled look-ahead steps have landed too
-  __syncthreads();   // all waves are done with the stage buffers the patches overlay
-  unsigned char* patch = smem + wave * S::EPI_WAVE_BYTES;
+  __syncthreads();   // nobody reads the rings any more, and nothing is on its way into them
+  take_stamp(2);
+  if (has_next) {    // uniform: open the next tile now, its loads run under the conversion and the stores
+    aim_at(npm * BM, npn * BN);
+    open_tile();
+  }
+  // Lane (r = lane % 16, g = lane / 16) holds, for every block (bi, bj), C[16 bi + r][16 bj + 4 g + 0..3]:
+  // 8 bytes once converted.  v_permlane16_swap exchanges the odd 16-lane rows of one register with the
+  // even rows of another; applied to the registers of blocks bj = 2p and 2p + 1 it leaves every lane with
+  // 16 contiguous bytes: lanes g = 0, 2 hold columns 0..7, 8..15 of block 2p, lanes g = 1, 3 those of block
+  // 2p + 1, so the four lanes of a row cover 64 contiguous bytes.
+  const int er = lane & 15, eg = lane >> 4;
+  const int ecol = n0 + wn * (TN * 16) + ((eg & 1) ? 16 + 4 * (eg - 1) : 4 * eg);     // + 32 p
+  static_assert(TN == 2 || TN == 4, "the register epilogue pairs up column blocks");
 #pragma unroll
   for (int bi = 0; bi < TM; ++bi) {
+    u32x4 chunk[TN / 2];
 #pragma unroll
-    for (int bj = 0; bj < TN; ++bj) {
-      bf16x4 h;
+    for (int p = 0; p < TN / 2; ++p) {
+      uint32_t d[2][2];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) h[e] = (__bf16)acc[bi][bj][e];
-      const int r = 16 * bi + (lane & 15);
-      const int ccol = 16 * bj + 4 * (lane >> 4);
-      *reinterpret_cast<bf16x4*>(patch + r * S::EPI_PITCH + ccol * 2) = h;
+      for (int h = 0; h < 2; ++h) {
+        bf16x4 c4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c4[e] = (__bf16)acc[bi][2 * p + h][e];
+        const auto two = __builtin_bit_cast(__attribute__((ext_vector_type(2))) uint32_t, c4);
+        d[h][0] = two[0];
+        d[h][1] = two[1];
+      }
+#pragma unroll
+      for (int w = 0; w < 2; ++w) {
+        const auto sw = __builtin_amdgcn_permlane16_swap(d[0][w], d[1][w], false, false);
+        d[0][w] = sw[0];
+        d[1][w] = sw[1];
+      }
+      chunk[p] = u32x4{d[0][0], d[0][1], d[1][0], d[1][1]};
+    }
+    const int row0 = m0 + wm * (TM * 16) + 16 * bi;
+    if constexpr (TN == 4) {
+      // Whole 128-byte lines per store instruction: lanes r and r + 8 trade one chunk (a rotation by 8 inside
+      // the 16-lane row), after which the first instruction writes rows 0..7 of the block (lanes r < 8 the
+      // left 64 bytes, lanes r >= 8 the right 64 bytes) and the second one rows 8..15.
+      const bool low = er < 8;
+      u32x4 give, got, s0, s1;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) give[e] = low ? chunk[1][e] : chunk[0][e];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) got[e] = __builtin_amdgcn_mov_dpp(give[e], 0x128 /* row_ror:8 */, 0xf, 0xf, false);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        s0[e] = low ? chunk[0][e] : got[e];
+        s1[e] = low ? got[e] : chunk[1][e];
+      }
+      const int col = ecol + (low ? 0 : 32);
+      const int row = row0 + (er & 7);
+      // C is written once and not read again by this kernel: streaming (non-temporal) stores
+      if (row < M && col < N) __builtin_nontemporal_store(s0, reinterpret_cast<u32x4*>(C + (size_t)row * N + col));
+      if (row + 8 < M && col < N) __builtin_nontemporal_store(s1, reinterpret_cast<u32x4*>(C + (size_t)(row + 8) * N + col));
+    } else {
+      const int row = row0 + er;
+      if (row < M && ecol < N) __builtin_nontemporal_store(chunk[0], reinterpret_cast<u32x4*>(C + (size_t)row * N + ecol));
     }
   }
-  __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this wave's patch is written (wave-private, no barrier)
-  constexpr int ROW_CHUNKS = TN * 16 * 2 / 16;      // 16-byte chunks per patch row
-  constexpr int ROWS_PER_PASS = 64 / ROW_CHUNKS;
-  const int er = lane / ROW_CHUNKS, ec = lane % ROW_CHUNKS;
+  take_stamp(3);
+  if constexpr (PROBE) {
+    if (tid == 0) {
 #pragma unroll
-  for (int p = 0; p < TM * 16 / ROWS_PER_PASS; ++p) {
-    const int r = p * ROWS_PER_PASS + er;
-    const u32x4 v = *reinterpret_cast<const u32x4*>(patch + r * S::EPI_PITCH + ec * 16);
-    const int row = m0 + wm * (TM * 16) + r;
-    const int col = n0 + wn * (TN * 16) + ec * 8;
-    // C is written once and not read again by this kernel: streaming (non-temporal) stores
-    if (row < M && col < N) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(C + (size_t)row * N + col));
+      for (int i = 0; i < 8; ++i) probe[i] = stamp[i];
+      probe[8] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11));      // XCC_ID
+      probe[9] = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));      // HW_ID
+      probe[10] = (uint64_t)KT;
+      probe[11] = (uint64_t)pm;
+      probe[12] = (uint64_t)pn;
+      probe[13] = probe[14] = probe[15] = 0;
+    }
   }
 }
 
@@ -447,13 +534,28 @@ __global__ __launch_bounds__(S::NT) void gemm_bf16_kernel(const uint16_t* __rest
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   int pm, pn;
   swz_decode_tile((int)blockIdx.x, grid_m, grid_n, num_xcd, group_m, MODE, &pm, &pn);
-  gemm_tile<S>(A, B, C, M, N, K, pm, pn, smem);
+  gemm_tile<S>(A, B, C, M, N, K, pm, pn, false, false, 0, 0, smem);
+}
+
+// The same kernel with time stamps (measurement aid): workgroup w also writes kProbeWords 64-bit words
+// at probe + w*kProbeWords.
+template <class S, int MODE>
+__global__ __launch_bounds__(S::NT) void gemm_bf16_probe_kernel(const uint16_t* __restrict__ A,
+                                                                const uint16_t* __restrict__ B,
+                                                                uint16_t* __restrict__ C, int M, int N, int K,
+                                                                int grid_m, int grid_n, int num_xcd, int group_m,
+                                                                uint64_t* __restrict__ probe) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  int pm, pn;
+  swz_decode_tile((int)blockIdx.x, grid_m, grid_n, num_xcd, group_m, MODE, &pm, &pn);
+  gemm_tile<S, true>(A, B, C, M, N, K, pm, pn, false, false, 0, 0, smem, probe + (size_t)blockIdx.x * kProbeWords);
 }
 
 // Persistent grid: gridDim.x workgroups (one per compute unit) stay resident; workgroup w is
 // renumbered among the workgroups and walks the raster with stride gridDim.x, the launch style
 // of the paper's GEMM case study (Appendix "Case Study: GEMM Swizzling", num_blocks = number of
-// compute units).
+// compute units).  A workgroup knows its next tile while it computes the current one, so the next
+// tile's opening loads are in flight while the current tile is converted and stored.
 template <class S, int MODE>
 __global__ __launch_bounds__(S::NT) void gemm_bf16_persistent_kernel(const uint16_t* __restrict__ A,
                                                                      const uint16_t* __restrict__ B,
@@ -461,13 +563,20 @@ __global__ __launch_bounds__(S::NT) void gemm_bf16_persistent_kernel(const uint1
                                                                      int grid_m, int grid_n, int num_xcd, int group_m) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int total = grid_m * grid_n;
-  for (int round = 0;; ++round) {
-    const int l = swz_persistent_logical((int)blockIdx.x, round, (int)gridDim.x, total, num_xcd, MODE);
-    if (l < 0) break;                      // uniform: the whole workgroup leaves together
-    int pm, pn;
-    swz_raster(l, grid_m, grid_n, group_m, swz_mode_grouped(MODE), &pm, &pn);
-    gemm_tile<S>(A, B, C, M, N, K, pm, pn, smem);
-    __syncthreads();                       // the next tile's loads overwrite LDS the epilogue read
+  int l = swz_persistent_logical((int)blockIdx.x, 0, (int)gridDim.x, total, num_xcd, MODE);
+  if (l < 0) return;                       // uniform: the whole workgroup leaves together
+  int pm, pn;
+  swz_raster(l, grid_m, grid_n, group_m, swz_mode_grouped(MODE), &pm, &pn);
+  bool staged = false;
+  for (int round = 1;; ++round) {
+    const int ln = swz_persistent_logical((int)blockIdx.x, round, (int)gridDim.x, total, num_xcd, MODE);
+    int npm = 0, npn = 0;
+    if (ln >= 0) swz_raster(ln, grid_m, grid_n, group_m, swz_mode_grouped(MODE), &npm, &npn);
+    gemm_tile<S>(A, B, C, M, N, K, pm, pn, staged, ln >= 0, npm, npn, smem);
+    if (ln < 0) break;
+    pm = npm;
+    pn = npn;
+    staged = true;
   }
 }
 

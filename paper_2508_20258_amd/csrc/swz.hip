@@ -126,6 +126,27 @@ int launch_gemm(const void* A, const void* B, void* C, int M, int N, int K, int 
   }
 }
 
+template <class S>
+int launch_gemm_probe(const void* A, const void* B, void* C, int M, int N, int K, int grid_m, int grid_n, int num_xcd,
+                      int group_m, int mode, uint64_t* probe, hipStream_t stream) {
+  auto go = [&](auto kernel) {
+    // set on every call: this is a measurement aid, not a hot path
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            S::LDS_BYTES) != hipSuccess)
+      return (int)SWZ_ERR_HIP;
+    return launch(kernel, dim3((unsigned)(grid_m * grid_n)), dim3(S::NT), S::LDS_BYTES, stream,
+                  static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(B), static_cast<uint16_t*>(C), M, N, K,
+                  grid_m, grid_n, num_xcd, group_m, probe);
+  };
+  switch (mode) {
+    case SWZ_MODE_RR: return go(swz::gemm_bf16_probe_kernel<S, kModeRR>);
+    case SWZ_MODE_XCD: return go(swz::gemm_bf16_probe_kernel<S, kModeXcd>);
+    case SWZ_MODE_XCD_GROUPM: return go(swz::gemm_bf16_probe_kernel<S, kModeXcdGroupM>);
+    case SWZ_MODE_GROUPM: return go(swz::gemm_bf16_probe_kernel<S, kModeGroupM>);
+    default: return SWZ_ERR_INVALID_ARG;
+  }
+}
+
 int resolve_plan(int64_t M, int64_t N, int64_t K, const swz_params* p, swz_params* r, int* grid_m, int* grid_n) {
   if (M < 1 || N < 1 || K < 1) return SWZ_ERR_INVALID_ARG;
   const int64_t lim = (int64_t)1 << 31;
@@ -390,27 +411,50 @@ int swz_gemm_plan(int64_t M, int64_t N, int64_t K, const swz_params* params, swz
   return resolve_plan(M, N, K, params, resolved, grid_m, grid_n);
 }
 
-int swz_gemm_ex(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,
-                const swz_params* params, hipStream_t stream) {
+// Checks shared by the GEMM entry points; on success r, grid_m, grid_n and group_m describe the launch.
+static int check_gemm(const void* A, const void* B, const void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,
+                      const swz_params* params, swz_params* r, int* grid_m, int* grid_n, int* group_m) {
   if (A == nullptr || B == nullptr || C == nullptr || !valid_mode(mode)) return SWZ_ERR_INVALID_ARG;
-  swz_params r;
-  int grid_m = 0, grid_n = 0;
-  int st = resolve_plan(M, N, K, params, &r, &grid_m, &grid_n);
+  int st = resolve_plan(M, N, K, params, r, grid_m, grid_n);
   if (st != SWZ_OK) return st;
   if (dtype != SWZ_DTYPE_BF16) return SWZ_ERR_UNSUPPORTED;
   if ((K % 8) != 0 || (N % 8) != 0) return SWZ_ERR_UNSUPPORTED;   // 16-byte vector loads along k and n
   // per-lane source offsets inside a tile step are 32-bit: (bm-1) rows of A, 31 rows of B
-  if ((int64_t)r.bm * K * 2 >= ((int64_t)1 << 32) || (int64_t)32 * N * 2 >= ((int64_t)1 << 32)) return SWZ_ERR_OVERFLOW;
+  if ((int64_t)r->bm * K * 2 >= ((int64_t)1 << 32) || (int64_t)32 * N * 2 >= ((int64_t)1 << 32)) return SWZ_ERR_OVERFLOW;
   if ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(C)) & 15)
     return SWZ_ERR_UNSUPPORTED;
-  int group_m = r.group_m;
-  st = check_map_args(grid_m, grid_n, r.num_xcd, &group_m, mode);
+  *group_m = r->group_m;
+  return check_map_args(*grid_m, *grid_n, r->num_xcd, group_m, mode);
+}
+
+int swz_gemm_ex(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,
+                const swz_params* params, hipStream_t stream) {
+  swz_params r;
+  int grid_m = 0, grid_n = 0, group_m = 0;
+  const int st = check_gemm(A, B, C, M, N, K, dtype, mode, params, &r, &grid_m, &grid_n, &group_m);
   if (st != SWZ_OK) return st;
   if (r.bm == 128)
     return launch_gemm<swz::GemmShape<128, 128, 2, 4>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
                                                                group_m, mode, r.num_wg, stream, 0);
   return launch_gemm<swz::GemmShape<256, 256, 2, 4>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
                                                              group_m, mode, r.num_wg, stream, 1);
+}
+
+int swz_gemm_probe(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,
+                   const swz_params* params, uint64_t* probe, int64_t probe_words, hipStream_t stream) {
+  if (probe == nullptr) return SWZ_ERR_INVALID_ARG;
+  swz_params r;
+  int grid_m = 0, grid_n = 0, group_m = 0;
+  const int st = check_gemm(A, B, C, M, N, K, dtype, mode, params, &r, &grid_m, &grid_n, &group_m);
+  if (st != SWZ_OK) return st;
+  if (r.persistent) return SWZ_ERR_UNSUPPORTED;
+  if (probe_words < (int64_t)grid_m * grid_n * swz::kProbeWords) return SWZ_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(probe) & 7) return SWZ_ERR_UNSUPPORTED;
+  if (r.bm == 128)
+    return launch_gemm_probe<swz::GemmShape<128, 128, 2, 4>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
+                                                                     group_m, mode, probe, stream);
+  return launch_gemm_probe<swz::GemmShape<256, 256, 2, 4>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
+                                                                   group_m, mode, probe, stream);
 }
 
 int swz_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,

@@ -42,3 +42,115 @@ def test_json_summary_splits_by_xcc(tmp_path):
     assert r["n"] == 1
     assert r["counters"]["TCC_HIT"]["total"] == 73 and r["counters"]["TCC_HIT"]["per_xcc"] == [3, 70]
     assert r["counters"]["TCC_MISS"]["per_xcc"] == [1, 30]
+
+
+# ---------------------------------------------------------------------------- candidate ranking (no GPU: canned child outputs)
+
+def _row(mode, g, tile, hit, model=80.0, panels=100, valid=True, us=100.0):
+    return dict(mode=mode, group_m=g, tile=tile, valid=valid, l2_hit_pct=hit, model_hit_pct=model, model_panels=panels, us_per_launch=us)
+
+
+def test_check_line_parser():
+    ok = "ran 30 warm-up + 20 timed launches\ncheck: bit_identical_to_rr=True map_is_permutation=True us_per_launch=93.125\n"
+    assert harness.parse_check_line(ok) == (True, 93.125)
+    assert harness.parse_check_line(ok.replace("rr=True", "rr=False"))[0] is False
+    assert harness.parse_check_line(ok.replace("permutation=True", "permutation=False"))[0] is False
+    valid, us = harness.parse_check_line("Traceback (most recent call last):\n  boom\n")     # the child died: not a valid candidate
+    assert valid is False and us != us
+
+
+def test_ranking_drops_broken_remaps_and_orders_by_measured_hit_rate():
+    rows = [_row("rr", None, 256, 48.5), _row("xcd", None, 256, 80.3), _row("xcd_groupm", 4, 256, 80.2),
+            _row("groupm", 8, 256, 99.0, valid=False),                      # highest hit rate, but its bits differ: broken remap
+            _row("groupm", 2, 256, None),                                    # profiler pass failed: no measurement
+            _row("groupm", 4, 256, float("nan"))]
+    good, best, tied = harness.rank_candidates(rows)
+    assert [r["mode"] for r in good] == ["xcd", "xcd_groupm", "rr"]
+    assert all(r["valid"] for r in good)
+    # 80.3 and 80.2 are within half a point: a tie, which the library default wins although it measured 0.1 lower and is not faster
+    assert (best["mode"], best["group_m"]) == ("xcd_groupm", 4) and [r["mode"] for r in tied] == ["xcd"]
+    assert harness.rank_candidates([_row("rr", None, 256, 70.0, valid=False)]) == ([], None, [])
+
+
+def test_ranking_ties_are_broken_by_the_panel_model_not_by_timing():
+    rows = [_row("groupm", 2, 256, 79.48, panels=3000, us=90.0),             # fastest by a hair: must not matter
+            _row("xcd_groupm", 8, 256, 79.47, panels=2000, us=99.0),         # fewest panels predicted: wins the tie
+            _row("xcd_groupm", 4, 256, 79.40, panels=3000, us=95.0),
+            _row("rr", None, 256, 70.7, panels=4000, us=89.0)]
+    good, best, tied = harness.rank_candidates(rows)
+    assert (best["mode"], best["group_m"]) == ("xcd_groupm", 8)
+    assert {(r["mode"], r["group_m"]) for r in tied} == {("groupm", 2), ("xcd_groupm", 4)}
+    # with equal predictions the library default is kept, and after it the simpler mapping
+    for r in rows:
+        r["model_panels"] = 3000
+    _, best, _ = harness.rank_candidates(rows)
+    assert (best["mode"], best["group_m"]) == ("xcd_groupm", 4)
+    _, best, _ = harness.rank_candidates([r for r in rows if r["group_m"] != 4])
+    assert best["mode"] == "groupm"
+    # outside the tie window the measurement decides, whatever the model says
+    rows[3]["l2_hit_pct"], rows[3]["model_panels"] = 85.0, 9999
+    _, best, tied = harness.rank_candidates(rows)
+    assert best["mode"] == "rr" and tied == []
+
+
+def test_candidate_list_spans_mode_group_and_tile():
+    c = harness.candidate_list([1, 4], [256, 128])
+    assert len(c) == 2 * (2 + 2 * 2) and ("xcd_groupm", 4, 128) in c and ("rr", 0, 256) in c
+    assert {t for _, _, t in c} == {256, 128}
+
+
+def test_harness_panel_model_agrees_with_the_oracles_on_library_maps():
+    # two independent implementations (the package never imports the oracle): same counts on the workload grids
+    import paper_2508_20258_amd as swz
+    from oracle import l2_model, pid_map as opm
+    for gm, gn in [(16, 16), (32, 32), (64, 8), (40, 28), (79, 55), (4, 4), (5, 7)]:
+        for mode in range(4):
+            for slots in (32, 64, 5):
+                lib_map = swz.pid_map(gm, gn, 8, 4, mode)
+                got, distinct, requested = harness.panel_model(lib_map, gn, 8, slots)
+                assert abs(got - l2_model.predicted_hit_rate(opm.pid_map(gm, gn, 8, 4, mode), gn, 8, slots)) < 1e-12
+                assert requested == 2 * gm * gn and 0 < distinct <= requested
+    assert harness.co_resident_tiles_per_xcd(256, 256, 8) == 32 and harness.co_resident_tiles_per_xcd(128, 256, 8) == 64
+
+
+def test_recorded_counters_are_tied_to_the_kernel_sources(tmp_path, monkeypatch):
+    rec = tmp_path / "measured_counters.json"
+    monkeypatch.setattr(harness, "RECORD_PATH", str(rec))
+    assert harness.recorded_counters() is None                                 # nothing recorded
+    rec.write_text(json.dumps({"kernel_sha256": harness.kernel_hash(), "workloads": {"cfg2_4096": {"rr": {"l2_hit_pct": 70.7}}}}))
+    assert harness.recorded_counters("cfg2_4096")["rr"]["l2_hit_pct"] == 70.7
+    assert harness.recorded_counters("cfg3_8192") is None
+    rec.write_text(json.dumps({"kernel_sha256": "0" * 64, "workloads": {"cfg2_4096": {}}}))
+    assert harness.recorded_counters("cfg2_4096") is None                      # another kernel's counters are not reported
+
+
+def test_csv_summary_last_n(tmp_path):
+    d = tmp_path / "run"
+    os.makedirs(d)
+    rows = "".join(f'"KERNEL_DISPATCH","gemm<2>",{1000 * i},{1000 * i + (500 if i < 6 else 100)}\n' for i in range(10))
+    (d / "1_kernel_trace.csv").write_text('"Kind","Kernel_Name","Start_Timestamp","End_Timestamp"\n' + rows)
+    assert harness.summarize(str(d), "gemm", last=4)["gemm<2>"]["warm_avg_ns"] == 100       # the timed launches only
+    assert harness.summarize(str(d), "gemm")["gemm<2>"]["warm_avg_ns"] == (500 + 4 * 100) / 5
+    assert len(harness.summarize_spans(str(d), "gemm")) == 10
+
+
+def test_clocks_report_on_hand_made_stamps():
+    import numpy as np
+    # two XCDs, two workgroups each; XCD 1 runs its loop at 1500 MHz, XCD 0 at 2000 MHz; 100 steps of 1100 cycles
+    rows = []
+    for w in range(4):
+        x = w % 2
+        mhz = 2000 if x == 0 else 1500
+        cyc = 100 * 1100
+        ticks = int(round(cyc / mhz * 100))                  # 100 MHz ticks the loop lasts
+        c0, r0 = 10_000 + w, 500 + w
+        rows.append([c0, r0, c0 + 4000, r0 + 200, c0 + 4000 + cyc, r0 + 200 + ticks, c0 + 4000 + cyc + 2000, r0 + 200 + ticks + 100,
+                     x, 0, 100, w // 2, w % 2, 0, 0, 0])
+    text = harness.clocks_report(np.array(rows), 1e9, "label")
+    lines = text.splitlines()
+    x0 = next(l for l in lines if l.startswith("  0 ")).split()
+    x1 = next(l for l in lines if l.startswith("  1 ")).split()
+    assert x0[1] == "2" and float(x0[2]) == 1100.0 and abs(float(x0[5]) - 2000) <= 2
+    assert float(x1[2]) == 1100.0 and abs(float(x1[5]) - 1500) <= 2
+    assert float(x1[9]) > float(x0[9])                     # the slower XCD's loop lasts longer
+    assert "slowest XCD 15" in lines[-1] and "fastest 20" in lines[-1]

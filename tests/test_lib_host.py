@@ -18,7 +18,8 @@ def test_library_exports_every_declared_entry_point():
     declared = set(re.findall(r"\b(swz_[a-z_]+)\s*\(", header))
     assert declared == {"swz_status_string", "swz_device_info", "swz_pid_map", "swz_pid_map_device", "swz_gemm",
                         "swz_gemm_ex", "swz_gemm_plan", "swz_copy_bytes", "swz_pid_map_persistent",
-                        "swz_pid_map_persistent_device", "swz_transpose", "swz_softmax", "swz_layernorm", "swz_mfma_peak"}
+                        "swz_pid_map_persistent_device", "swz_transpose", "swz_softmax", "swz_layernorm", "swz_mfma_peak",
+                        "swz_gemm_probe"}
     raw = ctypes.CDLL(swz.binding.LIB_PATH)
     for name in declared:
         assert hasattr(raw, name), name
