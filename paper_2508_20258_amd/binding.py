@@ -180,7 +180,7 @@ def gemm(a, b, c=None, mode: int = MODE_XCD_GROUPM, stream=None, **params):
 PROBE_WORDS = 16
 
 
-def gemm_probe(a, b, c=None, mode: int = MODE_XCD_GROUPM, stream=None, **params):
+def gemm_probe(a, b, c=None, mode: int = MODE_XCD_GROUPM, stream=None, probe=None, **params):
     """swz_gemm_probe: C = A @ B by the time-stamping instantiation of the kernel.
 
     Returns (c, probe): probe is an int64 CUDA tensor of shape (workgroups, 16), row w written by hardware
@@ -195,7 +195,9 @@ def gemm_probe(a, b, c=None, mode: int = MODE_XCD_GROUPM, stream=None, **params)
     assert c.is_cuda and c.dtype == torch.bfloat16 and c.is_contiguous() and tuple(c.shape) == (M, N)
     _same_current_device(stream, a, b, c)
     plan = gemm_plan(M, N, K, **params)
-    probe = torch.full((plan["grid_m"] * plan["grid_n"], PROBE_WORDS), -1, dtype=torch.int64, device=a.device)
+    if probe is None:
+        probe = torch.full((plan["grid_m"] * plan["grid_n"], PROBE_WORDS), -1, dtype=torch.int64, device=a.device)
+    assert probe.is_cuda and probe.is_contiguous() and probe.dtype == torch.int64
     p = _params(**params)
     _check(lib.swz_gemm_probe(a.data_ptr(), b.data_ptr(), c.data_ptr(), M, N, K, DTYPE_BF16, int(mode), ctypes.byref(p),
                               probe.data_ptr(), probe.numel(), _stream_handle(stream)), "swz_gemm_probe")

@@ -12,10 +12,13 @@ candidate search of the paper's optimisation loop without the LLM.
     python -m paper_2508_20258_amd.harness peak
     python -m paper_2508_20258_amd.harness summarize <rocprofv3 output dir>
 
-`run` launches one mapping mode of one workload: `--warmup` untimed launches (the clock of an idle
-device ramps up over the first milliseconds), then `--launches` timed ones; in a kernel trace of
-such a run the timed launches are the last `--launches` dispatches of the kernel, which is what
-`profile` averages.  `copy` launches the plain copy kernel of known HBM
+`run` launches one mapping mode of one workload: untimed warm-up launches worth `--warmup-ms` of GPU
+time, then `--launches` timed ones; in a kernel trace of such a run the timed launches are the last
+`--launches` dispatches of the kernel, which is what `profile` averages.  The warm-up has to outlast
+the power controller's transient: a device coming out of idle runs this kernel at boost clocks for
+about 2 ms (92 us per 4096^3 launch), is then throttled well below its sustained rate (up to 130 us
+around 3-4 ms) and settles after about 10 ms; numbers taken inside that window are not the
+sustained ones.  `copy` launches the plain copy kernel of known HBM
 traffic, against which FETCH_SIZE / WRITE_SIZE are scaled.  `profile` runs every rocprofv3 pass for
 the three mappings of a workload as child processes and prints the table kept under profiles/;
 `--record` also stores the counters, keyed by the SHA-256 of the kernel sources, where bench.py
@@ -103,6 +106,12 @@ def co_resident_tiles_per_xcd(tile, compute_units, num_xcd):
     return (compute_units // num_xcd) * (1 if tile >= 256 else 2)
 
 
+def warmup_launches(warmup_ms, flops):
+    """Launches that keep the device busy for about warmup_ms (priced at 1000 TFLOP/s, at least 10 us per launch)."""
+    per_launch_ms = max(flops / 1.0e15 * 1e3, 0.010)
+    return max(3, int(warmup_ms / per_launch_ms + 0.5))
+
+
 def cmd_run(args):
     import numpy as np
     import torch
@@ -118,17 +127,17 @@ def cmd_run(args):
     if args.persistent:
         params.update(persistent=1)
     mode = swz.MODES[args.mode]
-    for _ in range(max(args.warmup, 1)):            # untimed: first launch is cold, the clock ramps up over the next ones
-        swz.gemm(a, b, c, mode=mode, **params)
-    torch.cuda.synchronize()
+    warm = warmup_launches(args.warmup_ms, 2.0 * a.shape[0] * a.shape[1] * b.shape[1])
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(warm):                           # untimed; no synchronisation between these and the timed launches
+        swz.gemm(a, b, c, mode=mode, **params)
     e0.record()
     for _ in range(args.launches):
         swz.gemm(a, b, c, mode=mode, **params)
     e1.record()
     torch.cuda.synchronize()
     us = e0.elapsed_time(e1) * 1e3 / args.launches
-    print(f"ran {args.warmup} warm-up + {args.launches} timed launches of {args.workload} mode {args.mode}: {us:.2f} us per launch", flush=True)
+    print(f"ran {warm} warm-up + {args.launches} timed launches of {args.workload} mode {args.mode}: {us:.2f} us per launch", flush=True)
     if args.check:
         # remap purity: the bits must equal those of the round-robin launch; the map must be a permutation
         ref = torch.empty_like(c)
@@ -224,12 +233,12 @@ def cmd_rank(args):
                   f"(more than {args.prune_points:g} points under the best prediction)", flush=True)
             continue
         extra = ["--mode", r["mode"], "--tile", str(r["tile"])] + (["--group-m", str(r["group_m"])] if r["group_m"] else [])
-        chk = subprocess.run(me + extra + ["--check", "--warmup", "30", "--launches", "20"], cwd=root, env=env, capture_output=True, text=True, timeout=600)
+        chk = subprocess.run(me + extra + ["--check", "--warmup-ms", "40", "--launches", "20"], cwd=root, env=env, capture_output=True, text=True, timeout=600)
         r["valid"], r["us_per_launch"] = parse_check_line(chk.stdout)
         out = tempfile.mkdtemp(prefix="swz_rank_")
         try:
             prof = subprocess.run(["rocprofv3", "--pmc", "TCC_HIT", "TCC_MISS", "--output-format", "json", "-d", out, "--"]
-                                  + me + extra + ["--warmup", "1", "--launches", "2"],
+                                  + me + extra + ["--warmup-ms", "0", "--launches", "2"],
                                   cwd=root, env=env, capture_output=True, text=True, timeout=600)
             if prof.returncode == 0:
                 for d in summarize_json(out, "gemm").values():
@@ -271,7 +280,7 @@ def _one(directory, kernel, last=0):
     return next(iter(r.values())) if r else None
 
 
-def profile_table(src, workload, warmup, launches, num_xcd=8, compute_units=256):
+def profile_table(src, workload, warmup_ms, launches, num_xcd=8, compute_units=256):
     """Text table and counter record from the rocprofv3 output directories `profile` wrote under src."""
     import seeded_inputs as si
 
@@ -290,18 +299,19 @@ def profile_table(src, workload, warmup, launches, num_xcd=8, compute_units=256)
              "MI355X (gfx950), one GPU.  Written by (repository root, TMPDIR=/tmp):",
              f"  {H} profile --workload {workload} --out <dir>",
              "which runs, for MODE in rr, xcd, xcd_groupm:",
-             f"  rocprofv3 --kernel-trace --stats --output-format csv -d <out> -- {run} --warmup {warmup} --launches {launches}",
-             f"  rocprofv3 --pmc TCC_HIT TCC_MISS --output-format json -d <out> -- {run} --warmup 1 --launches 3",
-             f"  rocprofv3 --pmc FETCH_SIZE --output-format csv -d <out> -- {run} --warmup 1 --launches 3     (then the same with WRITE_SIZE)",
-             f"  rocprofv3 --pmc {' '.join(SQ_COUNTERS)} --output-format csv -d <out> -- {run} --warmup 1 --launches 3",
+             f"  rocprofv3 --kernel-trace --stats --output-format csv -d <out> -- {run} --warmup-ms {warmup_ms:g} --launches {launches}",
+             f"  rocprofv3 --pmc TCC_HIT TCC_MISS --output-format json -d <out> -- {run} --warmup-ms 0 --launches 3",
+             f"  rocprofv3 --pmc FETCH_SIZE --output-format csv -d <out> -- {run} --warmup-ms 0 --launches 3     (then the same with WRITE_SIZE)",
+             f"  rocprofv3 --pmc {' '.join(SQ_COUNTERS)} --output-format csv -d <out> -- {run} --warmup-ms 0 --launches 3",
              f"  rocprofv3 --pmc FETCH_SIZE --output-format csv -d <out> -- {H} copy --mib 1024 --launches 3     (calibration; then WRITE_SIZE)",
              f"Byte-counter calibration on the plain 1 GiB copy kernel: FETCH_SIZE read {copy_f:.0f} KiB, WRITE_SIZE read {copy_w:.0f} KiB for 1048576 KiB",
              f"  => scale FETCH_SIZE by {fs:.3f}, WRITE_SIZE by {ws:.3f}.  Algorithmic minimum HBM bytes 2(MK+KN+MN) = {2 * (M * K + K * N + M * N) / 2 ** 20:.1f} MiB.",
              "L2 hit = TCC_HIT/(TCC_HIT+TCC_MISS) over all TCC instances; per XCD = the instances of each DIMENSION_XCC.",
              f"model = lock-step panel-count prediction on swz_pid_map's output, {co_resident_tiles_per_xcd(bm, compute_units, num_xcd)} co-resident tiles per XCD.",
-             f"us = average kernel duration in the kernel trace over the last {launches} dispatches (the timed launches; the {warmup} warm-up launches before them are not averaged);",
-             "cold us = the same over the first 10 dispatches of the run (device idle before).  event us = the run's own event timing per launch (includes launch gaps).", ""]
-    lines.append(f"{'mode':11s} {'us':>9s} {'cold us':>9s} {'event us':>9s} {'TFLOP/s':>8s} {'%peak':>6s} {'L2 hit%':>8s} {'model%':>7s} {'fetch MiB':>10s} {'write MiB':>10s} "
+             f"us = average kernel duration in the kernel trace over the last {launches} dispatches (the timed launches; the warm-up launches before them, {warmup_ms:g} ms of GPU time, are not averaged);",
+             "first us = the same over the first 10 dispatches of the run (device idle before: boost clocks); worst us = the slowest dispatch of the run (the power controller's",
+             "throttling a few milliseconds in).  event us = the run's own event timing per timed launch (includes launch gaps).", ""]
+    lines.append(f"{'mode':11s} {'us':>9s} {'first us':>9s} {'worst us':>9s} {'event us':>9s} {'TFLOP/s':>8s} {'%peak':>6s} {'L2 hit%':>8s} {'model%':>7s} {'fetch MiB':>10s} {'write MiB':>10s} "
                  f"{'MfmaUtil%':>9s} {'LDS confl%':>10s}  per-XCD L2 hit %")
     record = {}
     for mode in PROFILE_MODES:
@@ -310,6 +320,7 @@ def profile_table(src, workload, warmup, launches, num_xcd=8, compute_units=256)
         us = kt["warm_avg_ns"] / 1e3
         spans = sorted(summarize_spans(f"{t}_kt", "gemm"))
         cold = sum(d for _, d in spans[:10]) / max(len(spans[:10]), 1) / 1e3
+        worst = max(d for _, d in spans) / 1e3
         ev = float("nan")
         try:
             with open(f"{t}_kt.log") as f:
@@ -330,7 +341,7 @@ def profile_table(src, workload, warmup, launches, num_xcd=8, compute_units=256)
         confl = 100 * sq["SQ_LDS_BANK_CONFLICT"] / sq["SQ_LDS_IDX_ACTIVE"]
         tile_map = swz.pid_map(gm, gn, num_xcd, 4, swz.MODES[mode])
         model = 100 * panel_model(tile_map, gn, num_xcd, co_resident_tiles_per_xcd(bm, compute_units, num_xcd))[0]
-        lines.append(f"{mode:11s} {us:9.2f} {cold:9.2f} {ev:9.2f} {tf:8.1f} {tf / 25:6.1f} {hit:8.2f} {model:7.1f} {fkib / 1024:10.1f} {wkib / 1024:10.1f} "
+        lines.append(f"{mode:11s} {us:9.2f} {cold:9.2f} {worst:9.2f} {ev:9.2f} {tf:8.1f} {tf / 25:6.1f} {hit:8.2f} {model:7.1f} {fkib / 1024:10.1f} {wkib / 1024:10.1f} "
                      f"{util:9.1f} {confl:10.2f}  " + " ".join(f"{r:.1f}" for r in per))
         record[mode] = dict(kernel_us=us, l2_hit_pct=hit, l2_hit_pct_per_xcd=per, model_hit_pct=model, fetch_bytes=int(fkib * 1024),
                             write_bytes=int(wkib * 1024), mfma_util_pct=util,
@@ -354,6 +365,7 @@ def summarize_spans(directory, kernel_filter):
 def cmd_profile(args):
     """Every rocprofv3 pass for the three mappings of one workload, as child processes; prints the summary table."""
     import json
+    import shutil
     import subprocess
     env = dict(os.environ, TMPDIR=os.environ.get("TMPDIR", "/tmp"))
     root = os.path.dirname(HERE)
@@ -363,6 +375,7 @@ def cmd_profile(args):
 
     def rocprof(tag, fmt, prof_args, prog_args, limit=180):
         d = os.path.join(out, tag)
+        shutil.rmtree(d, ignore_errors=True)          # a pass directory holds one run: the readers sum over every file they find
         res = subprocess.run(["rocprofv3", *prof_args, "--output-format", fmt, "-d", d, "--", *me, *prog_args],
                              cwd=root, env=env, capture_output=True, text=True, timeout=limit)
         with open(d + ".log", "w") as f:
@@ -376,14 +389,14 @@ def cmd_profile(args):
             rocprof(tag, "csv", ["--pmc", c], ["copy", "--mib", "1024", "--launches", "3"])
         for mode in PROFILE_MODES:
             run = ["run", "--workload", args.workload, "--mode", mode]
-            short = run + ["--warmup", "1", "--launches", "3"]
+            short = run + ["--warmup-ms", "0", "--launches", "3"]
             t = f"{args.workload}_{mode}"
-            rocprof(t + "_kt", "csv", ["--kernel-trace", "--stats"], run + ["--warmup", str(args.warmup), "--launches", str(args.launches)])
+            rocprof(t + "_kt", "csv", ["--kernel-trace", "--stats"], run + ["--warmup-ms", str(args.warmup_ms), "--launches", str(args.launches)])
             rocprof(t + "_tcc", "json", ["--pmc", "TCC_HIT", "TCC_MISS"], short)
             rocprof(t + "_fetch", "csv", ["--pmc", "FETCH_SIZE"], short)
             rocprof(t + "_write", "csv", ["--pmc", "WRITE_SIZE"], short)
             rocprof(t + "_sq", "csv", ["--pmc", *SQ_COUNTERS], short)
-    text, record = profile_table(out, args.workload, args.warmup, args.launches)
+    text, record = profile_table(out, args.workload, args.warmup_ms, args.launches)
     print(text, flush=True)
     with open(os.path.join(out, f"gemm_{args.workload}.txt"), "w") as f:
         f.write(text)
@@ -459,20 +472,20 @@ def cmd_clocks(args):
     c = torch.empty((a.shape[0], b.shape[1]), dtype=torch.bfloat16, device="cuda")
     mode = swz.MODES[args.mode]
     params = dict(bm=args.tile, bn=args.tile) if args.tile else {}
-    for _ in range(args.warmup):
-        swz.gemm(a, b, c, mode=mode, **params)
-    for _ in range(3):                                     # the stamped kernel itself, warm
-        _, probe = swz.gemm_probe(a, b, c, mode=mode, **params)
+    flops = 2.0 * a.shape[0] * a.shape[1] * b.shape[1]
+    _, probe = swz.gemm_probe(a, b, c, mode=mode, **params)          # loads the stamped kernel's code before the measurement
     torch.cuda.synchronize()
+    warm = warmup_launches(args.warmup_ms, flops)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(warm):                                  # the product kernel; the stamped launch follows without a gap
+        swz.gemm(a, b, c, mode=mode, **params)
     e0.record()
-    _, probe = swz.gemm_probe(a, b, c, mode=mode, **params)
+    swz.gemm_probe(a, b, c, mode=mode, probe=probe, **params)
     e1.record()
     torch.cuda.synchronize()
     us = e0.elapsed_time(e1) * 1e3
-    flops = 2.0 * a.shape[0] * a.shape[1] * b.shape[1]
-    label = (f"swz_gemm_probe, workload {args.workload}, mode {args.mode}, after {args.warmup} warm-up launches; "
-             f"the stamped launch took {us:.2f} us between events ({flops / us / 1e6:.0f} TFLOP/s)")
+    label = (f"swz_gemm_probe, workload {args.workload}, mode {args.mode}, launched right behind {warm} warm-up launches "
+             f"({args.warmup_ms:g} ms) of the product kernel; the stamped launch took {us:.2f} us between events ({flops / us / 1e6:.0f} TFLOP/s)")
     print(clocks_report(probe.cpu().numpy(), flops, label), flush=True)
 
 
@@ -677,7 +690,7 @@ def main(argv=None):
     r.add_argument("--workload", default="cfg2_4096")
     r.add_argument("--mode", default="xcd_groupm", choices=["rr", "xcd", "xcd_groupm", "groupm"])
     r.add_argument("--launches", type=int, default=20, help="timed launches")
-    r.add_argument("--warmup", type=int, default=50, help="untimed launches before the timed ones")
+    r.add_argument("--warmup-ms", type=float, default=40.0, help="GPU time of untimed launches before the timed ones")
     r.add_argument("--tile", type=int, default=0)
     r.add_argument("--group-m", type=int, default=0)
     r.add_argument("--persistent", action="store_true")
@@ -694,7 +707,7 @@ def main(argv=None):
     pf = sub.add_parser("profile")
     pf.add_argument("--workload", default="cfg2_4096")
     pf.add_argument("--out", required=True)
-    pf.add_argument("--warmup", type=int, default=50)
+    pf.add_argument("--warmup-ms", type=float, default=40.0)
     pf.add_argument("--launches", type=int, default=20)
     pf.add_argument("--record", action="store_true", help="store the counters, keyed by the kernel source hash, for bench.py")
     pf.add_argument("--table-only", action="store_true", help="only rebuild the table from passes already under --out")
@@ -703,7 +716,7 @@ def main(argv=None):
     ck.add_argument("--workload", default="cfg2_4096")
     ck.add_argument("--mode", default="xcd_groupm", choices=["rr", "xcd", "xcd_groupm", "groupm"])
     ck.add_argument("--tile", type=int, default=0)
-    ck.add_argument("--warmup", type=int, default=50)
+    ck.add_argument("--warmup-ms", type=float, default=40.0)
     ck.set_defaults(fn=cmd_clocks)
     t = sub.add_parser("transpose")
     t.add_argument("--m", type=int, default=16384)

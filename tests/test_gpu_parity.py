@@ -466,7 +466,7 @@ def test_harness_run_check_as_a_child_process():
     from paper_2508_20258_amd import harness
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     cmd = [sys.executable, "-m", "paper_2508_20258_amd.harness", "run", "--workload", "cfg1_512", "--mode", "xcd_groupm",
-           "--group-m", "2", "--tile", "128", "--warmup", "3", "--launches", "5", "--check"]
+           "--group-m", "2", "--tile", "128", "--warmup-ms", "1", "--launches", "5", "--check"]
     res = subprocess.run(cmd, cwd=root, capture_output=True, text=True, timeout=300)
     assert res.returncode == 0, res.stderr[-2000:]
     valid, us = harness.parse_check_line(res.stdout)
