@@ -12,11 +12,25 @@ rows is walked column by column before the next band starts) is likewise built a
 list.  No closed form of the library appears in this file.
 
 Modes: 0 = identity + row-major, 1 = XCD renumbering + row-major,
-       2 = XCD renumbering + grouped-M, 3 = identity + grouped-M.
+       2 = XCD renumbering + grouped-M, 3 = identity + grouped-M;
+       + 4 (MODE_SKEW) = the same with a skewed raster: column pn of the tile grid is shifted down
+       cyclically by pn tile rows, so a run of consecutive raster positions that used to stay in one
+       tile row now walks a diagonal and touches as many different tile rows as tile columns.  Not in
+       the paper either: it is aimed at the memory channels, not at the L2 (a transpose of a matrix
+       whose row pitch is a power of two writes a whole tile row's worth of tiles into the same few
+       channels); as a PID remap it is judged by the paper's own criterion, bijectivity.
 """
 from __future__ import annotations
 
 MODE_RR, MODE_XCD, MODE_XCD_GROUPM, MODE_GROUPM = 0, 1, 2, 3
+MODE_SKEW = 4
+VALID_MODES = tuple(range(8))
+
+
+def mode_parts(mode: int) -> tuple[bool, bool, bool]:
+    """(XCD renumbering?, grouped-M raster?, skewed raster?) of a mode."""
+    base = mode % 4
+    return base in (MODE_XCD, MODE_XCD_GROUPM), base in (MODE_XCD_GROUPM, MODE_GROUPM), mode >= MODE_SKEW
 
 
 def deal_round_robin(num_wg: int, num_xcd: int) -> list[list[int]]:
@@ -40,31 +54,45 @@ def logical_ids(num_wg: int, num_xcd: int, xcd_remap: bool) -> list[int]:
     return l_of_w
 
 
-def raster_order(grid_m: int, grid_n: int, group_m: int, grouped: bool) -> list[tuple[int, int]]:
+def shift_columns_down(order: list[tuple[int, int]], grid_m: int) -> list[tuple[int, int]]:
+    """The skew: every tile of column pn moves down pn tile rows, wrapping around at the bottom."""
+    moved = []
+    for pm, pn in order:
+        new_row = pm
+        for _ in range(pn):                             # one row at a time, so that nothing but "down, wrap" is used
+            new_row += 1
+            if new_row == grid_m:
+                new_row = 0
+        moved.append((new_row, pn))
+    return moved
+
+
+def raster_order(grid_m: int, grid_n: int, group_m: int, grouped: bool, skewed: bool = False) -> list[tuple[int, int]]:
     """order[l] = (pm, pn): the tile visited l-th."""
     order: list[tuple[int, int]] = []
     if not grouped:
         for pm in range(grid_m):
             for pn in range(grid_n):
                 order.append((pm, pn))
-        return order
-    first = 0
-    while first < grid_m:
-        rows_in_band = min(group_m, grid_m - first)     # the last band may be shorter
-        for pn in range(grid_n):
-            for pm in range(first, first + rows_in_band):
-                order.append((pm, pn))
-        first += group_m
-    return order
+    else:
+        first = 0
+        while first < grid_m:
+            rows_in_band = min(group_m, grid_m - first)     # the last band may be shorter
+            for pn in range(grid_n):
+                for pm in range(first, first + rows_in_band):
+                    order.append((pm, pn))
+            first += group_m
+    return shift_columns_down(order, grid_m) if skewed else order
 
 
 def pid_map(grid_m: int, grid_n: int, num_xcd: int, group_m: int, mode: int) -> list[int]:
     """out[w] = pm * grid_n + pn, the output tile that hardware workgroup w computes."""
-    if grid_m < 1 or grid_n < 1 or num_xcd < 1 or group_m < 1 or mode not in (0, 1, 2, 3):
+    if grid_m < 1 or grid_n < 1 or num_xcd < 1 or group_m < 1 or mode not in VALID_MODES:
         raise ValueError("bad arguments")
     num_wg = grid_m * grid_n
-    l_of_w = logical_ids(num_wg, num_xcd, xcd_remap=mode in (MODE_XCD, MODE_XCD_GROUPM))
-    order = raster_order(grid_m, grid_n, group_m, grouped=mode in (MODE_XCD_GROUPM, MODE_GROUPM))
+    renumber, grouped, skewed = mode_parts(mode)
+    l_of_w = logical_ids(num_wg, num_xcd, xcd_remap=renumber)
+    order = raster_order(grid_m, grid_n, group_m, grouped, skewed)
     out = []
     for w in range(num_wg):
         pm, pn = order[l_of_w[w]]
@@ -79,11 +107,12 @@ def pid_map_persistent(grid_m: int, grid_n: int, num_xcd: int, group_m: int, mod
     The workgroups (not the tiles) are dealt to the XCDs and renumbered XCD by XCD; workgroup w with
     new number p then takes the raster positions p, p + num_wg, p + 2*num_wg, ...
     """
-    if grid_m < 1 or grid_n < 1 or num_xcd < 1 or group_m < 1 or num_wg < 1 or mode not in (0, 1, 2, 3):
+    if grid_m < 1 or grid_n < 1 or num_xcd < 1 or group_m < 1 or num_wg < 1 or mode not in VALID_MODES:
         raise ValueError("bad arguments")
     total = grid_m * grid_n
-    p_of_w = logical_ids(num_wg, num_xcd, xcd_remap=mode in (MODE_XCD, MODE_XCD_GROUPM))
-    order = raster_order(grid_m, grid_n, group_m, grouped=mode in (MODE_XCD_GROUPM, MODE_GROUPM))
+    renumber, grouped, skewed = mode_parts(mode)
+    p_of_w = logical_ids(num_wg, num_xcd, xcd_remap=renumber)
+    order = raster_order(grid_m, grid_n, group_m, grouped, skewed)
     rounds = []
     start = 0
     while start < total:
@@ -122,7 +151,8 @@ def xcd_tile_sets(out, num_xcd: int) -> list[list[int]]:
     return [[int(out[w]) for w in bucket] for bucket in deal_round_robin(len(out), num_xcd)]
 
 
-def fair_share(out, grid_m: int, grid_n: int, group_m: int, grouped: bool, num_xcd: int, renumbered: bool) -> bool:
+def fair_share(out, grid_m: int, grid_n: int, group_m: int, grouped: bool, num_xcd: int, renumbered: bool,
+               skewed: bool = False) -> bool:
     """Every XCD works on its fair share of the raster, judged on the map itself.
 
     The tile count T comes from the grid, never from len(out).  XCD x (the workgroups w with
@@ -134,7 +164,7 @@ def fair_share(out, grid_m: int, grid_n: int, group_m: int, grouped: bool, num_x
     holds a position of another XCD's share all fail.
     """
     total = grid_m * grid_n
-    order = raster_order(grid_m, grid_n, group_m, grouped)
+    order = raster_order(grid_m, grid_n, group_m, grouped, skewed)
     pos = {pm * grid_n + pn: l for l, (pm, pn) in enumerate(order)}
     if len(out) != total:
         return False
@@ -157,9 +187,10 @@ def fair_share(out, grid_m: int, grid_n: int, group_m: int, grouped: bool, num_x
     return len(claimed) == total
 
 
-def xcd_runs_contiguous(out, grid_m: int, grid_n: int, group_m: int, grouped: bool, num_xcd: int) -> bool:
+def xcd_runs_contiguous(out, grid_m: int, grid_n: int, group_m: int, grouped: bool, num_xcd: int,
+                        skewed: bool = False) -> bool:
     """Each XCD's tiles are one contiguous, increasing run of the raster order, runs abutting in XCD order."""
-    order = raster_order(grid_m, grid_n, group_m, grouped)
+    order = raster_order(grid_m, grid_n, group_m, grouped, skewed)
     pos = {pm * grid_n + pn: l for l, (pm, pn) in enumerate(order)}
     expect = 0
     for tiles in xcd_tile_sets(out, num_xcd):

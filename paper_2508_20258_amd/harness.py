@@ -168,7 +168,7 @@ TIE_POINTS = 0.5                                    # measured hit rates closer 
 
 
 def rank_candidates(rows, tie_points=TIE_POINTS):
-    """Order measured candidates and pick the best validated one.
+    """Order measured candidates of ONE tile shape and pick the best validated one.
 
     rows: dicts with mode, group_m, tile, valid, l2_hit_pct (measured), model_hit_pct, model_panels, us_per_launch.
     Broken candidates (valid false) and candidates without a measured hit rate are dropped.  The rest is
@@ -185,11 +185,24 @@ def rank_candidates(rows, tie_points=TIE_POINTS):
     tied = [r for r in good if top - r["l2_hit_pct"] <= tie_points]
 
     def key(r):
-        is_default = (r["mode"], r.get("group_m") or 4, r.get("tile") or 256) == DEFAULT_CANDIDATE
-        return (r.get("model_panels", 0), 0 if is_default else 1, simplicity.get(r["mode"], 9), r.get("group_m") or 0, -(r.get("tile") or 256))
+        is_default = (r["mode"], r.get("group_m") or 4) == DEFAULT_CANDIDATE[:2]
+        return (r.get("model_panels", 0), 0 if is_default else 1, simplicity.get(r["mode"], 9), r.get("group_m") or 0)
     tied.sort(key=key)
     best = tied[0]
     return good, best, [r for r in tied if r is not best]
+
+
+def pick_across_tiles(winners):
+    """The winner among the per-tile-shape winners.  A hit rate is a ratio of requests, and a smaller tile asks the
+    L2 for more lines per flop, so rates of different tile shapes do not compare; what they stand for does: the bytes
+    that missed (TCC_MISS lines of 128 bytes), i.e. what crossed the fabric.  Fewest missed bytes wins; without that
+    figure, the fewest predicted panel bytes."""
+    winners = [w for w in winners if w is not None]
+    if not winners:
+        return None
+    if all(w.get("l2_miss_mib") is not None for w in winners):
+        return min(winners, key=lambda w: w["l2_miss_mib"])
+    return min(winners, key=lambda w: w.get("model_panels", 0))
 
 
 def candidate_list(group_ms, tiles):
@@ -224,13 +237,14 @@ def cmd_rank(args):
         hit, panels, _ = panel_model(m, plan["grid_n"], X, co_resident_tiles_per_xcd(tile, args.compute_units, X))
         rows.append(dict(mode=mode, group_m=g or None, tile=tile, model_hit_pct=100.0 * hit,
                          model_panels=panels * tile, valid=None, l2_hit_pct=None, us_per_launch=None))
-    # 2. measure, most promising first; candidates the model puts far below the best are skipped (never the round-robin ones)
-    rows.sort(key=lambda r: -r["model_hit_pct"])
-    best_model = rows[0]["model_hit_pct"]
+    # 2. measure, most promising first; within a tile shape, candidates the model puts far below that shape's best are
+    #    skipped (never the round-robin one: it is the baseline every candidate is validated against)
+    rows.sort(key=lambda r: (-r["tile"], -r["model_hit_pct"]))
+    best_model = {t: max(r["model_hit_pct"] for r in rows if r["tile"] == t) for t in args.tile}
     for r in rows:
-        if r["mode"] != "rr" and best_model - r["model_hit_pct"] > args.prune_points:
+        if r["mode"] != "rr" and best_model[r["tile"]] - r["model_hit_pct"] > args.prune_points:
             print(f"candidate {r['mode']:11s} group_m={r['group_m'] or '-':>2} tile {r['tile']}: model {r['model_hit_pct']:5.1f} %  skipped "
-                  f"(more than {args.prune_points:g} points under the best prediction)", flush=True)
+                  f"(more than {args.prune_points:g} points under the best prediction for this tile shape)", flush=True)
             continue
         extra = ["--mode", r["mode"], "--tile", str(r["tile"])] + (["--group-m", str(r["group_m"])] if r["group_m"] else [])
         chk = subprocess.run(me + extra + ["--check", "--warmup-ms", "40", "--launches", "20"], cwd=root, env=env, capture_output=True, text=True, timeout=600)
@@ -249,21 +263,28 @@ def cmd_rank(args):
             shutil.rmtree(out, ignore_errors=True)
         hit = r["l2_hit_pct"] if r["l2_hit_pct"] is not None else float("nan")
         print(f"candidate {r['mode']:11s} group_m={r['group_m'] or '-':>2} tile {r['tile']}: valid={r['valid']}  model {r['model_hit_pct']:5.1f} %  "
-              f"measured L2 hit {hit:6.2f} %  missed lines {r.get('l2_miss_mib', float('nan')):8.1f} MiB  {r['us_per_launch']:9.2f} us", flush=True)
+              f"measured L2 hit {hit:6.2f} %  missed {r.get('l2_miss_mib', float('nan')):8.1f} MiB  {r['us_per_launch']:9.2f} us", flush=True)
     measured = [r for r in rows if r["valid"] is not None]
-    good, best, tied = rank_candidates(measured)
-    dropped = [r for r in measured if not r["valid"]]
-    for r in dropped:
-        print(f"dropped (broken remap): {r['mode']} group_m={r['group_m']} tile {r['tile']}")
-    print(f"ranking by measured L2 hit rate (within {TIE_POINTS} points = tie; ties broken by the panel model, then library default, then simplicity):")
-    for r in good:
-        print(f"  {r['mode']:11s} group_m={r['group_m'] or '-':>2} tile {r['tile']}  measured {r['l2_hit_pct']:6.2f} %  model {r['model_hit_pct']:5.1f} %  {r['us_per_launch']:9.2f} us")
+    for r in measured:
+        if not r["valid"]:
+            print(f"dropped (broken remap): {r['mode']} group_m={r['group_m']} tile {r['tile']}")
+    winners = []
+    for tile in args.tile:
+        good, best, tied = rank_candidates([r for r in measured if r["tile"] == tile])
+        print(f"tile {tile}: ranking by measured L2 hit rate (within {TIE_POINTS} points = tie; ties broken by the panel model, then library default, then simplicity):")
+        for r in good:
+            print(f"  {r['mode']:11s} group_m={r['group_m'] or '-':>2}  measured {r['l2_hit_pct']:6.2f} %  model {r['model_hit_pct']:5.1f} %  "
+                  f"missed {r.get('l2_miss_mib', float('nan')):8.1f} MiB  {r['us_per_launch']:9.2f} us")
+        if best:
+            print(f"  best of tile {tile}: {best['mode']} group_m={best['group_m']}"
+                  + (" (tied with: " + ", ".join(f"{r['mode']}/g{r['group_m'] or '-'}" for r in tied) + ")" if tied else ""))
+        winners.append(best)
+    best = pick_across_tiles(winners)
     if best:
-        print("best validated candidate: " + json.dumps(best))
-        if tied:
-            print("tied with it: " + ", ".join(f"{r['mode']}/g{r['group_m'] or '-'}/t{r['tile']}" for r in tied))
+        print("best validated candidate (across tile shapes: fewest bytes missed in L2): " + json.dumps(best))
+        good = [r for r in measured if r["valid"]]
         fastest = min(good, key=lambda r: r["us_per_launch"])
-        print(f"fastest candidate (timing of 20 launches, for information): {fastest['mode']} group_m={fastest['group_m']} tile {fastest['tile']} "
+        print(f"fastest candidate (event timing of 20 launches, for information): {fastest['mode']} group_m={fastest['group_m']} tile {fastest['tile']} "
               f"{fastest['us_per_launch']:.2f} us")
 
 
@@ -498,6 +519,9 @@ def cmd_transpose(args):
     out = torch.empty((args.n, args.m), dtype=torch.bfloat16, device="cuda")
     mode = swz.MODES[args.mode]
     params = dict(group_m=args.group_m) if args.group_m else {}
+    if args.block:
+        params.update(bm=args.block[0], bn=args.block[1])
+        args.tile = 0
     swz.transpose(x, out, tile=args.tile, mode=mode, **params)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -508,7 +532,8 @@ def cmd_transpose(args):
     torch.cuda.synchronize()
     us = e0.elapsed_time(e1) * 1e3 / max(args.launches - 1, 1)
     gbs = 4.0 * args.m * args.n / (us * 1e-6) / 1e9
-    print(f"ran {args.launches} transposes {args.m}x{args.n} tile {args.tile} mode {args.mode} group_m {args.group_m or 4}: {us:.2f} us per launch, "
+    shape = f"{args.block[0]}x{args.block[1]}" if args.block else str(args.tile)
+    print(f"ran {args.launches} transposes {args.m}x{args.n} tile {shape} mode {args.mode} group_m {args.group_m or 4}: {us:.2f} us per launch, "
           f"{gbs:.0f} GB/s of 4*M*N bytes ({100 * gbs / 8000:.1f} % of 8 TB/s)", flush=True)
 
 
@@ -722,6 +747,8 @@ def main(argv=None):
     t.add_argument("--m", type=int, default=16384)
     t.add_argument("--n", type=int, default=16384)
     t.add_argument("--tile", type=int, default=128, choices=[32, 64, 128])
+    t.add_argument("--block", type=int, nargs=2, default=None, metavar=("ROWS", "COLS"),
+                   help="rectangular block of the input per workgroup instead of a square tile: 256 64, 256 128, 512 64, 512 128")
     t.add_argument("--mode", default="xcd_groupm", choices=["rr", "xcd", "xcd_groupm", "groupm"])
     t.add_argument("--launches", type=int, default=10)
     t.add_argument("--group-m", type=int, default=0)

@@ -93,6 +93,17 @@ def test_ranking_ties_are_broken_by_the_panel_model_not_by_timing():
     assert best["mode"] == "rr" and tied == []
 
 
+def test_tile_shapes_are_compared_by_missed_bytes_not_by_hit_rate():
+    # a 128-wide tile asks for twice the lines per flop: its hit rate reads higher although more bytes cross the fabric
+    small = dict(_row("groupm", 2, 128, 82.8), l2_miss_mib=362.8)
+    big = dict(_row("xcd_groupm", 4, 256, 79.5), l2_miss_mib=224.0)
+    assert harness.pick_across_tiles([small, big]) is big
+    assert harness.pick_across_tiles([small, None]) is small and harness.pick_across_tiles([None]) is None
+    del small["l2_miss_mib"]                                                 # no measurement: the model's panel bytes decide
+    small["model_panels"], big["model_panels"] = 200, 100
+    assert harness.pick_across_tiles([small, big]) is big
+
+
 def test_candidate_list_spans_mode_group_and_tile():
     c = harness.candidate_list([1, 4], [256, 128])
     assert len(c) == 2 * (2 + 2 * 2) and ("xcd_groupm", 4, 128) in c and ("rr", 0, 256) in c

@@ -171,7 +171,7 @@ def test_fair_share_sizes_against_brute_force_counts(T, X):
 
 
 def test_bad_arguments_raise():
-    for args in [(0, 4, 8, 4, 0), (4, 0, 8, 4, 0), (4, 4, 0, 4, 1), (4, 4, 8, 0, 2), (4, 4, 8, 4, 4), (4, 4, 8, 4, -1)]:
+    for args in [(0, 4, 8, 4, 0), (4, 0, 8, 4, 0), (4, 4, 0, 4, 1), (4, 4, 8, 0, 2), (4, 4, 8, 4, 8), (4, 4, 8, 4, -1)]:
         with pytest.raises(ValueError):
             opm.pid_map(*args)
 
@@ -224,3 +224,77 @@ def test_persistent_with_one_workgroup_per_tile_equals_the_plain_map():
     for gm, gn, X, g in [(4, 5, 4, 2), (6, 7, 8, 4), (3, 3, 8, 4)]:
         for mode in range(4):
             assert opm.pid_map_persistent(gm, gn, X, g, mode, gm * gn) == [opm.pid_map(gm, gn, X, g, mode)]
+
+
+# ---------------------------------------------------------------------------- skewed raster (modes 4..7)
+
+@pytest.mark.parametrize("gm,gn", [(1, 1), (1, 7), (7, 1), (4, 4), (5, 3), (3, 5), (8, 8), (6, 10), (16, 16), (9, 31)])
+def test_skew_is_a_cyclic_roll_of_every_grid_column(gm, gn):
+    # independent route: lay the unskewed raster positions out as a grid_m x grid_n array; the skew rolls
+    # column c down by c (numpy's roll), nothing else
+    import numpy as np
+    for grouped in (False, True):
+        g = 3
+        plain = opm.raster_order(gm, gn, g, grouped, False)
+        pos = np.full((gm, gn), -1)
+        for l, (pm, pn) in enumerate(plain):
+            pos[pm, pn] = l
+        rolled = np.stack([np.roll(pos[:, c], c) for c in range(gn)], axis=1)
+        skewed = opm.raster_order(gm, gn, g, grouped, True)
+        for l, (pm, pn) in enumerate(skewed):
+            assert rolled[pm, pn] == l
+        assert sorted(skewed) == sorted(plain)                      # still every tile exactly once
+        assert [pn for _, pn in skewed] == [pn for _, pn in plain]  # tiles never change their column
+
+
+def test_skew_special_cases_and_the_diagonal_property():
+    # one column: nothing moves; skew of a square row-major raster: every raster row is a full diagonal
+    assert opm.raster_order(6, 1, 2, False, True) == opm.raster_order(6, 1, 2, False, False)
+    n = 8
+    order = opm.raster_order(n, n, 1, False, True)
+    for r in range(n):
+        row = order[r * n:(r + 1) * n]
+        assert sorted(pm for pm, _ in row) == list(range(n)) and [pn for _, pn in row] == list(range(n))
+        assert row[0] == (r, 0) and row[1] == ((r + 1) % n, 1)
+    # inside one raster row, a window of consecutive positions touches as many tile rows as tile columns (up to grid_m)
+    for gm, gn, width in [(16, 16, 10), (128, 128, 40), (5, 9, 9), (9, 5, 5), (3, 8, 6)]:
+        order = opm.raster_order(gm, gn, 1, False, True)
+        for r in range(gm):
+            for c0 in range(gn - width + 1):
+                w = order[r * gn + c0:r * gn + c0 + width]
+                assert len({pn for _, pn in w}) == width and len({pm for pm, _ in w}) == min(width, gm)
+    # the worked 4 x 5 example with the skew on top: XCD x, which owned tile row x, now owns a diagonal
+    want = [((x + c) % 4) * 5 + c for x in range(4) for c in range(5)]
+    got = opm.pid_map(4, 5, 4, 1, opm.MODE_XCD + opm.MODE_SKEW)
+    assert [got[w] for x in range(4) for w in range(x, 20, 4)] == want
+
+
+@pytest.mark.parametrize("gm,gn", [(4, 4), (16, 16), (40, 28), (79, 55), (5, 5), (7, 3), (1, 1), (2, 3), (128, 128)])
+@pytest.mark.parametrize("X", [1, 3, 8])
+@pytest.mark.parametrize("mode", [4, 5, 6, 7])
+def test_invariants_of_skewed_modes(gm, gn, X, mode):
+    g = 4
+    out = opm.pid_map(gm, gn, X, g, mode)
+    renumber, grouped, skewed = opm.mode_parts(mode)
+    assert skewed and opm.is_permutation(out, gm * gn)
+    assert opm.fair_share(out, gm, gn, g, grouped, X, renumber, skewed=True)
+    if renumber:
+        assert opm.xcd_runs_contiguous(out, gm, gn, g, grouped, X, skewed=True)
+        if gn > 1 and gm > 1:
+            assert not opm.xcd_runs_contiguous(out, gm, gn, g, grouped, X, skewed=False) or gm * gn <= X
+    # the skewed map is the unskewed one with every tile moved down its column, cyclically
+    plain = opm.pid_map(gm, gn, X, g, mode - 4)
+    assert out == [((t // gn + t % gn) % gm) * gn + t % gn for t in plain]
+
+
+def test_mode_parts_and_bad_modes():
+    assert [opm.mode_parts(m) for m in range(8)] == [(False, False, False), (True, False, False), (True, True, False),
+                                                     (False, True, False), (False, False, True), (True, False, True),
+                                                     (True, True, True), (False, True, True)]
+    for bad in (-1, 8, 12):
+        with pytest.raises(ValueError):
+            opm.pid_map(4, 4, 8, 4, bad)
+        with pytest.raises(ValueError):
+            opm.pid_map_persistent(4, 4, 8, 4, bad, 8)
+    rounds = opm.pid_map_persistent(5, 7, 8, 2, 6, 6)
+    assert opm.is_permutation([t for r in rounds for t in r if t >= 0], 35)
