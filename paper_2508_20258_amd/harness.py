@@ -519,9 +519,6 @@ def cmd_transpose(args):
     out = torch.empty((args.n, args.m), dtype=torch.bfloat16, device="cuda")
     mode = swz.MODES[args.mode]
     params = dict(group_m=args.group_m) if args.group_m else {}
-    if args.block:
-        params.update(bm=args.block[0], bn=args.block[1])
-        args.tile = 0
     swz.transpose(x, out, tile=args.tile, mode=mode, **params)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -532,8 +529,7 @@ def cmd_transpose(args):
     torch.cuda.synchronize()
     us = e0.elapsed_time(e1) * 1e3 / max(args.launches - 1, 1)
     gbs = 4.0 * args.m * args.n / (us * 1e-6) / 1e9
-    shape = f"{args.block[0]}x{args.block[1]}" if args.block else str(args.tile)
-    print(f"ran {args.launches} transposes {args.m}x{args.n} tile {shape} mode {args.mode} group_m {args.group_m or 4}: {us:.2f} us per launch, "
+    print(f"ran {args.launches} transposes {args.m}x{args.n} tile {args.tile} mode {args.mode} group_m {args.group_m or 4}: {us:.2f} us per launch, "
           f"{gbs:.0f} GB/s of 4*M*N bytes ({100 * gbs / 8000:.1f} % of 8 TB/s)", flush=True)
 
 
@@ -747,8 +743,6 @@ def main(argv=None):
     t.add_argument("--m", type=int, default=16384)
     t.add_argument("--n", type=int, default=16384)
     t.add_argument("--tile", type=int, default=128, choices=[32, 64, 128])
-    t.add_argument("--block", type=int, nargs=2, default=None, metavar=("ROWS", "COLS"),
-                   help="rectangular block of the input per workgroup instead of a square tile: 256 64, 256 128, 512 64, 512 128")
     t.add_argument("--mode", default="xcd_groupm", choices=["rr", "xcd", "xcd_groupm", "groupm"])
     t.add_argument("--launches", type=int, default=10)
     t.add_argument("--group-m", type=int, default=0)
