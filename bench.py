@@ -133,8 +133,8 @@ def other_kernels(swz, torch):
     us = time_calls(torch, lambda: swz.copy_bytes(x, y))
     copy_gbs = 4.0 * m * n / (us * 1e-6) / 1e9
     res[f"plain_copy_{m}x{n}"] = entry(us, m, n)
-    for tile in (128, 64, 32):
-        for mode in ("rr", "xcd_groupm"):
+    for tile in (64, 128, 32):
+        for mode in ("rr", "xcd_groupm", "xcd_groupm_skew"):
             us = time_calls(torch, lambda: swz.transpose(x, y, tile=tile, mode=swz.MODES[mode]))
             res[f"transpose_{m}x{n}_tile{tile}_{mode}"] = entry(us, m, n, copy_gbs)
     del x, y

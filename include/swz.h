@@ -37,7 +37,8 @@ typedef enum {
   SWZ_MODE_RR = 0,         /* no renumbering, row-major raster: what round-robin dispatch gives by default */
   SWZ_MODE_XCD = 1,        /* XCD renumbering (each XCD owns one contiguous run of the raster), row-major   */
   SWZ_MODE_XCD_GROUPM = 2, /* XCD renumbering, grouped-M raster                                            */
-  SWZ_MODE_GROUPM = 3      /* no renumbering, grouped-M raster                                             */
+  SWZ_MODE_GROUPM = 3,     /* no renumbering, grouped-M raster                                             */
+  SWZ_MODE_SKEW = 4        /* flag, may be added to any of the four: skewed raster, modes 4..7 (see swz_pid_map) */
 } swz_mode;
 
 typedef enum { SWZ_DTYPE_BF16 = 0 } swz_dtype; /* A, B, C bfloat16; accumulation in fp32 */
@@ -80,6 +81,12 @@ int swz_device_info(int* num_xcd, int* compute_units, int* l2_bytes, int* lds_by
  *   r = T mod X); its i-th workgroup (i = w div X) gets logical id  x*q + min(x,r) + i.
  *   Grouped raster of logical id l: bands of group_m tile rows (last band shorter), inside a
  *   band column by column, inside a column top to bottom.
+ *   Skew (mode + SWZ_MODE_SKEW; not one of the paper's patterns, but judged by its criterion for
+ *   a remap, bijectivity): the tile (pm, pn) the raster gives becomes ((pm + pn) mod grid_m, pn),
+ *   i.e. column pn of the grid is rotated down by pn tile rows, so consecutive raster positions
+ *   walk a diagonal.  For kernels whose tiles share nothing but whose tile rows collide in the
+ *   memory channels (swz_transpose on power-of-two pitches).  swz_softmax / swz_layernorm return
+ *   UNSUPPORTED for skewed modes; every other entry point that takes a mode accepts them.
  * Errors: INVALID_ARG (null out, any argument < 1, unknown mode), OVERFLOW (grid_m*grid_n >= 2^31). */
 int swz_pid_map(int grid_m, int grid_n, int num_xcd, int group_m, int mode, int32_t* out);
 
@@ -148,9 +155,9 @@ int swz_gemm_plan(int64_t M, int64_t N, int64_t K, const swz_params* params, swz
  * grid is ceil(M/tile) x ceil(N/tile) and hardware workgroup ids are turned into tiles exactly as
  * swz_pid_map does for that grid (`mode`, params->group_m, params->num_xcd; other fields ignored).
  *   in, out : caller-owned DEVICE pointers, 16-byte aligned, must not overlap.
- *   tile    : 128 (row segments of 256 bytes, the fastest), 64 (whole 128-byte lines) or 32 (half
- *             lines, shared between neighbouring tiles: the case where the mapping decides the L2
- *             hit rate).
+ *   tile    : 64 (whole 128-byte lines; the fastest together with mode SWZ_MODE_XCD_GROUPM +
+ *             SWZ_MODE_SKEW), 128 (row segments of 256 bytes) or 32 (half lines, shared between
+ *             neighbouring tiles: the case where the mapping decides the L2 hit rate).
  * Asynchronous on `stream`; never allocates or synchronises.
  * Errors: INVALID_ARG (null, M/N < 1, unknown mode), UNSUPPORTED (elem_bytes != 2, tile not 32/64/128,
  * M or N not a multiple of 8, misaligned pointer), OVERFLOW, HIP. */

@@ -13,7 +13,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libswz.so")
 
 MODE_RR, MODE_XCD, MODE_XCD_GROUPM, MODE_GROUPM = 0, 1, 2, 3
+MODE_SKEW = 4                          # flag: add to any of the four for the skewed raster (modes 4..7)
 MODES = {"rr": MODE_RR, "xcd": MODE_XCD, "xcd_groupm": MODE_XCD_GROUPM, "groupm": MODE_GROUPM}
+MODES.update({name + "_skew": m + MODE_SKEW for name, m in list(MODES.items())})
 DTYPE_BF16 = 0
 
 EXPORTS = ("swz_status_string", "swz_device_info", "swz_pid_map", "swz_pid_map_device", "swz_gemm", "swz_gemm_ex",
@@ -238,8 +240,9 @@ def pid_map_persistent_device(grid_m: int, grid_n: int, num_xcd: int, group_m: i
     return tile, xcc
 
 
-def transpose(x, out=None, tile: int = 128, mode: int = MODE_XCD_GROUPM, stream=None, **params):
-    """out (N x M) = x (M x N) transposed on the GPU through swz_transpose; 16-bit element tensors."""
+def transpose(x, out=None, tile: int = 64, mode: int = MODE_XCD_GROUPM + MODE_SKEW, stream=None, **params):
+    """out (N x M) = x (M x N) transposed on the GPU through swz_transpose; 16-bit element tensors.
+    The defaults (64-wide tiles, XCD renumbering + grouped raster + skew) are the fastest combination measured."""
     import torch
     assert x.is_cuda and x.is_contiguous() and x.dim() == 2 and x.element_size() == 2
     M, N = x.shape

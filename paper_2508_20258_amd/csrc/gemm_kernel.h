@@ -524,16 +524,17 @@ __device__ __forceinline__ void gemm_tile(const uint16_t* __restrict__ A, const 
   }
 }
 
-// One workgroup per tile.  MODE is a template parameter so that each mapping shows up under its
-// own kernel name in profiler traces; only the decode depends on it.
+// One workgroup per tile.  MODE (one of the four renumbering / raster combinations) is a template
+// parameter so that each mapping shows up under its own kernel name in profiler traces; the skew
+// comes as an argument; only the decode depends on either.
 template <class S, int MODE>
 __global__ __launch_bounds__(S::NT) void gemm_bf16_kernel(const uint16_t* __restrict__ A,
                                                           const uint16_t* __restrict__ B,
                                                           uint16_t* __restrict__ C, int M, int N, int K,
-                                                          int grid_m, int grid_n, int num_xcd, int group_m) {
+                                                          int grid_m, int grid_n, int num_xcd, int group_m, int skew) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   int pm, pn;
-  swz_decode_tile((int)blockIdx.x, grid_m, grid_n, num_xcd, group_m, MODE, &pm, &pn);
+  swz_decode_tile((int)blockIdx.x, grid_m, grid_n, num_xcd, group_m, MODE | (skew ? kModeSkew : 0), &pm, &pn);
   gemm_tile<S>(A, B, C, M, N, K, pm, pn, false, false, 0, 0, smem);
 }
 
@@ -544,10 +545,10 @@ __global__ __launch_bounds__(S::NT) void gemm_bf16_probe_kernel(const uint16_t* 
                                                                 const uint16_t* __restrict__ B,
                                                                 uint16_t* __restrict__ C, int M, int N, int K,
                                                                 int grid_m, int grid_n, int num_xcd, int group_m,
-                                                                uint64_t* __restrict__ probe) {
+                                                                int skew, uint64_t* __restrict__ probe) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   int pm, pn;
-  swz_decode_tile((int)blockIdx.x, grid_m, grid_n, num_xcd, group_m, MODE, &pm, &pn);
+  swz_decode_tile((int)blockIdx.x, grid_m, grid_n, num_xcd, group_m, MODE | (skew ? kModeSkew : 0), &pm, &pn);
   gemm_tile<S, true>(A, B, C, M, N, K, pm, pn, false, false, 0, 0, smem, probe + (size_t)blockIdx.x * kProbeWords);
 }
 
@@ -560,18 +561,20 @@ template <class S, int MODE>
 __global__ __launch_bounds__(S::NT) void gemm_bf16_persistent_kernel(const uint16_t* __restrict__ A,
                                                                      const uint16_t* __restrict__ B,
                                                                      uint16_t* __restrict__ C, int M, int N, int K,
-                                                                     int grid_m, int grid_n, int num_xcd, int group_m) {
+                                                                     int grid_m, int grid_n, int num_xcd, int group_m,
+                                                                     int skew) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int total = grid_m * grid_n;
+  const int mode = MODE | (skew ? kModeSkew : 0);
   int l = swz_persistent_logical((int)blockIdx.x, 0, (int)gridDim.x, total, num_xcd, MODE);
   if (l < 0) return;                       // uniform: the whole workgroup leaves together
   int pm, pn;
-  swz_raster(l, grid_m, grid_n, group_m, swz_mode_grouped(MODE), &pm, &pn);
+  swz_tile_at(l, grid_m, grid_n, group_m, mode, &pm, &pn);
   bool staged = false;
   for (int round = 1;; ++round) {
     const int ln = swz_persistent_logical((int)blockIdx.x, round, (int)gridDim.x, total, num_xcd, MODE);
     int npm = 0, npn = 0;
-    if (ln >= 0) swz_raster(ln, grid_m, grid_n, group_m, swz_mode_grouped(MODE), &npm, &npn);
+    if (ln >= 0) swz_tile_at(ln, grid_m, grid_n, group_m, mode, &npm, &npn);
     gemm_tile<S>(A, B, C, M, N, K, pm, pn, staged, ln >= 0, npm, npn, smem);
     if (ln < 0) break;
     pm = npm;
@@ -603,7 +606,7 @@ __global__ void pid_map_persistent_kernel(int grid_m, int grid_n, int num_xcd, i
     int t = -1;
     if (l >= 0) {
       int pm, pn;
-      swz_raster(l, grid_m, grid_n, group_m, swz_mode_grouped(mode), &pm, &pn);
+      swz_tile_at(l, grid_m, grid_n, group_m, mode, &pm, &pn);
       t = pm * grid_n + pn;
     }
     tile[(size_t)round * g + w] = t;
@@ -612,10 +615,20 @@ __global__ void pid_map_persistent_kernel(int grid_m, int grid_n, int num_xcd, i
 }
 
 // Plain streaming copy of n 16-byte words (reads n*16 bytes, writes n*16 bytes): a kernel of
-// known HBM traffic against which profiler byte counters are scaled.
+// known HBM traffic against which profiler byte counters are scaled, and the rate of which the
+// bandwidth-bound kernels are compared with.  Four loads are in flight per thread before the first
+// store; a workgroup moves 16 KiB of consecutive addresses per round.
 __global__ __launch_bounds__(256) void copy16_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int64_t n) {
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+  const int64_t stride = (int64_t)gridDim.x * 1024;
+  for (int64_t base = (int64_t)blockIdx.x * 1024 + threadIdx.x; base < n; base += stride) {
+    u32x4 v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (base + 256 * j < n) v[j] = __builtin_nontemporal_load(src + base + 256 * j);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (base + 256 * j < n) __builtin_nontemporal_store(v[j], dst + base + 256 * j);
+  }
 }
 
 }  // namespace swz

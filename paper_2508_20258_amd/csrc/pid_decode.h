@@ -16,6 +16,15 @@
 // group_m tile rows (the last band may be shorter, gsz rows); within a band l walks column
 // by column, top to bottom inside a column.  (k mod gsz, k div gsz) is the mixed-radix
 // decomposition of k in [0, gsz*grid_n), so each band, and hence the grid, is covered once.
+//
+// The skew (mode bit 4) moves the tile the raster produced down its own column by pn tile rows,
+// cyclically: (pm, pn) -> ((pm + pn) mod grid_m, pn).  For every pn this is a rotation of that
+// column, hence a bijection of the grid onto itself, and the composition with the raster stays a
+// bijection.  A run of consecutive raster positions that stayed in one tile row now walks a
+// diagonal.  It serves kernels whose tiles share no data but whose tile rows alias in the memory
+// channels: a transpose of a matrix with a power-of-two row pitch writes every tile of a tile row
+// into the same few channels, and tiles that run at the same time should therefore differ in
+// their tile row as well as in their tile column.
 #pragma once
 
 #include <stdint.h>
@@ -26,7 +35,7 @@
 #define SWZ_HD inline
 #endif
 
-enum : int { kModeRR = 0, kModeXcd = 1, kModeXcdGroupM = 2, kModeGroupM = 3 };
+enum : int { kModeRR = 0, kModeXcd = 1, kModeXcdGroupM = 2, kModeGroupM = 3, kModeSkew = 4, kModeCount = 8 };
 
 // XCD renumbering of id w among `total` ids dealt round-robin to num_xcd XCDs (see the proof above).
 // Requires 1 <= num_xcd, 0 <= w < total < 2^31.
@@ -56,15 +65,23 @@ SWZ_HD void swz_raster(int l, int grid_m, int grid_n, int group_m, bool grouped,
   }
 }
 
-SWZ_HD bool swz_mode_renumbers(int mode) { return mode == kModeXcd || mode == kModeXcdGroupM; }
-SWZ_HD bool swz_mode_grouped(int mode) { return mode == kModeXcdGroupM || mode == kModeGroupM; }
+SWZ_HD bool swz_mode_renumbers(int mode) { return (mode & 3) == kModeXcd || (mode & 3) == kModeXcdGroupM; }
+SWZ_HD bool swz_mode_grouped(int mode) { return (mode & 3) == kModeXcdGroupM || (mode & 3) == kModeGroupM; }
+SWZ_HD bool swz_mode_skewed(int mode) { return (mode & kModeSkew) != 0; }
+
+// Tile at raster position l under `mode` (raster, then the skew if the mode asks for it).
+// Requirements as swz_raster; pm + pn < 2^31 because grid_m*grid_n < 2^31.
+SWZ_HD void swz_tile_at(int l, int grid_m, int grid_n, int group_m, int mode, int* pm, int* pn) {
+  swz_raster(l, grid_m, grid_n, group_m, swz_mode_grouped(mode), pm, pn);
+  if (swz_mode_skewed(mode)) *pm = (*pm + *pn) % grid_m;
+}
 
 // One workgroup per tile.  Requires: 1 <= grid_m, grid_n, num_xcd; 1 <= group_m <= grid_m;
 // grid_m*grid_n < 2^31; 0 <= w < grid_m*grid_n.  All intermediate values are <= grid_m*grid_n.
 SWZ_HD void swz_decode_tile(int w, int grid_m, int grid_n, int num_xcd, int group_m, int mode, int* pm, int* pn) {
   const int total = grid_m * grid_n;
   const int l = swz_mode_renumbers(mode) ? swz_xcd_renumber(w, total, num_xcd) : w;
-  swz_raster(l, grid_m, grid_n, group_m, swz_mode_grouped(mode), pm, pn);
+  swz_tile_at(l, grid_m, grid_n, group_m, mode, pm, pn);
 }
 
 // Persistent grid (the launch style of the paper's own GEMM listing: num_blocks = number of

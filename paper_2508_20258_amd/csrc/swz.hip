@@ -83,7 +83,7 @@ int launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStrea
   return launch_impl(kernel, grid, block, lds, stream, vals, std::index_sequence_for<KArgs...>{});
 }
 
-bool valid_mode(int mode) { return mode >= SWZ_MODE_RR && mode <= SWZ_MODE_GROUPM; }
+bool valid_mode(int mode) { return mode >= 0 && mode < kModeCount; }
 
 // Shared checks of the two PID-map entry points.  Clamps group_m to grid_m (same raster).
 int check_map_args(int grid_m, int grid_n, int num_xcd, int* group_m, int mode) {
@@ -96,7 +96,7 @@ int check_map_args(int grid_m, int grid_n, int num_xcd, int* group_m, int mode) 
 // num_wg == 0: one workgroup per tile; otherwise the persistent kernel with num_wg workgroups.
 template <class S, int MODE>
 int launch_gemm_mode(const void* A, const void* B, void* C, int M, int N, int K, int grid_m, int grid_n,
-                     int num_xcd, int group_m, int num_wg, hipStream_t stream, int slot) {
+                     int num_xcd, int group_m, int skew, int num_wg, hipStream_t stream, int slot) {
   auto kernel = num_wg > 0 ? swz::gemm_bf16_persistent_kernel<S, MODE> : swz::gemm_bf16_kernel<S, MODE>;
   const int style = num_wg > 0 ? 1 : 0;
   int dev = 0;
@@ -111,18 +111,18 @@ int launch_gemm_mode(const void* A, const void* B, void* C, int M, int N, int K,
   }
   const unsigned blocks = (unsigned)(num_wg > 0 ? num_wg : grid_m * grid_n);
   return launch(kernel, dim3(blocks), dim3(S::NT), S::LDS_BYTES, stream, static_cast<const uint16_t*>(A),
-                static_cast<const uint16_t*>(B), static_cast<uint16_t*>(C), M, N, K, grid_m, grid_n, num_xcd, group_m);
+                static_cast<const uint16_t*>(B), static_cast<uint16_t*>(C), M, N, K, grid_m, grid_n, num_xcd, group_m, skew);
 }
 
 template <class S>
 int launch_gemm(const void* A, const void* B, void* C, int M, int N, int K, int grid_m, int grid_n,
                 int num_xcd, int group_m, int mode, int num_wg, hipStream_t stream, int slot) {
-  switch (mode) {
-    case SWZ_MODE_RR: return launch_gemm_mode<S, kModeRR>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, num_wg, stream, slot);
-    case SWZ_MODE_XCD: return launch_gemm_mode<S, kModeXcd>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, num_wg, stream, slot);
-    case SWZ_MODE_XCD_GROUPM: return launch_gemm_mode<S, kModeXcdGroupM>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, num_wg, stream, slot);
-    case SWZ_MODE_GROUPM: return launch_gemm_mode<S, kModeGroupM>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, num_wg, stream, slot);
-    default: return SWZ_ERR_INVALID_ARG;
+  const int skew = swz_mode_skewed(mode) ? 1 : 0;
+  switch (mode & 3) {
+    case SWZ_MODE_RR: return launch_gemm_mode<S, kModeRR>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, skew, num_wg, stream, slot);
+    case SWZ_MODE_XCD: return launch_gemm_mode<S, kModeXcd>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, skew, num_wg, stream, slot);
+    case SWZ_MODE_XCD_GROUPM: return launch_gemm_mode<S, kModeXcdGroupM>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, skew, num_wg, stream, slot);
+    default: return launch_gemm_mode<S, kModeGroupM>(A, B, C, M, N, K, grid_m, grid_n, num_xcd, group_m, skew, num_wg, stream, slot);
   }
 }
 
@@ -136,14 +136,13 @@ int launch_gemm_probe(const void* A, const void* B, void* C, int M, int N, int K
       return (int)SWZ_ERR_HIP;
     return launch(kernel, dim3((unsigned)(grid_m * grid_n)), dim3(S::NT), S::LDS_BYTES, stream,
                   static_cast<const uint16_t*>(A), static_cast<const uint16_t*>(B), static_cast<uint16_t*>(C), M, N, K,
-                  grid_m, grid_n, num_xcd, group_m, probe);
+                  grid_m, grid_n, num_xcd, group_m, swz_mode_skewed(mode) ? 1 : 0, probe);
   };
-  switch (mode) {
+  switch (mode & 3) {
     case SWZ_MODE_RR: return go(swz::gemm_bf16_probe_kernel<S, kModeRR>);
     case SWZ_MODE_XCD: return go(swz::gemm_bf16_probe_kernel<S, kModeXcd>);
     case SWZ_MODE_XCD_GROUPM: return go(swz::gemm_bf16_probe_kernel<S, kModeXcdGroupM>);
-    case SWZ_MODE_GROUPM: return go(swz::gemm_bf16_probe_kernel<S, kModeGroupM>);
-    default: return SWZ_ERR_INVALID_ARG;
+    default: return go(swz::gemm_bf16_probe_kernel<S, kModeGroupM>);
   }
 }
 
@@ -186,12 +185,12 @@ int launch_transpose(const void* in, void* out, int M, int N, int gm, int gn, in
   const dim3 grid((unsigned)(gm * gn)), block(256);
   auto* i = static_cast<const uint16_t*>(in);
   auto* o = static_cast<uint16_t*>(out);
-  switch (mode) {
-    case SWZ_MODE_RR: return launch(swz::transpose16_kernel<TILE, kModeRR>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m);
-    case SWZ_MODE_XCD: return launch(swz::transpose16_kernel<TILE, kModeXcd>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m);
-    case SWZ_MODE_XCD_GROUPM: return launch(swz::transpose16_kernel<TILE, kModeXcdGroupM>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m);
-    case SWZ_MODE_GROUPM: return launch(swz::transpose16_kernel<TILE, kModeGroupM>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m);
-    default: return SWZ_ERR_INVALID_ARG;
+  const int skew = swz_mode_skewed(mode) ? 1 : 0;
+  switch (mode & 3) {
+    case SWZ_MODE_RR: return launch(swz::transpose16_kernel<TILE, kModeRR>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m, skew);
+    case SWZ_MODE_XCD: return launch(swz::transpose16_kernel<TILE, kModeXcd>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m, skew);
+    case SWZ_MODE_XCD_GROUPM: return launch(swz::transpose16_kernel<TILE, kModeXcdGroupM>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m, skew);
+    default: return launch(swz::transpose16_kernel<TILE, kModeGroupM>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m, skew);
   }
 }
 // How the two row-wise entry points launch: threads per row (256, or 64 = one row per wave when a
@@ -203,6 +202,7 @@ struct RowPlan {
 
 int resolve_rows(int64_t M, int64_t N, int chunks, int mode, const swz_params* params, RowPlan* plan) {
   if (M < 1 || N < 1 || chunks < 1 || !valid_mode(mode)) return SWZ_ERR_INVALID_ARG;
+  if (swz_mode_skewed(mode)) return SWZ_ERR_UNSUPPORTED;   // a skew would pull the chunks of a row apart again
   const int64_t lim = (int64_t)1 << 31;
   if (M >= lim || N >= lim || M * chunks >= lim) return SWZ_ERR_OVERFLOW;
   if ((N % 8) != 0 || N > ((int64_t)1 << 24)) return SWZ_ERR_UNSUPPORTED;   // 16-byte vectors; fp32 element counts stay exact
@@ -310,7 +310,7 @@ int swz_pid_map_persistent(int grid_m, int grid_n, int num_xcd, int group_m, int
       int t = -1;
       if (l >= 0) {
         int pm, pn;
-        swz_raster(l, grid_m, grid_n, group_m, swz_mode_grouped(mode), &pm, &pn);
+        swz_tile_at(l, grid_m, grid_n, group_m, mode, &pm, &pn);
         t = pm * grid_n + pn;
       }
       out[(size_t)round * num_wg + w] = t;
@@ -400,7 +400,7 @@ int swz_copy_bytes(const void* src, void* dst, int64_t bytes, hipStream_t stream
   if (src == nullptr || dst == nullptr || bytes < 16) return SWZ_ERR_INVALID_ARG;
   if ((bytes & 15) || ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15)) return SWZ_ERR_UNSUPPORTED;
   const int64_t n = bytes / 16;
-  const int64_t want = (n + 255) / 256;
+  const int64_t want = (n + 1023) / 1024;                       // a workgroup moves 1024 words per round
   const unsigned blocks = (unsigned)(want < 8192 ? want : 8192);
   return launch(swz::copy16_kernel, dim3(blocks), dim3(256), 0, stream, static_cast<const swz::u32x4*>(src),
                 static_cast<swz::u32x4*>(dst), n);

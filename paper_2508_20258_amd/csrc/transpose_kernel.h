@@ -8,12 +8,18 @@
 // rows 0..3 of column i), so a lane ends up with 8 consecutive elements of one row of `out` and
 // stores them as 16 bytes.  The kernel is bound by HBM: 4*M*N bytes per launch.
 //
-// TILE = 128: row segments of 256 bytes on both sides; 9 % faster than 64 (longer runs per DRAM page).
+// TILE = 128: row segments of 256 bytes on both sides.
 // TILE = 64: every row segment read or written is one whole 128-byte line, so tiles share no
 //            lines and the mapping of tiles to XCDs cannot change the L2 hit rate.
 // TILE = 32: row segments are half lines; horizontally adjacent tiles share the lines they read
 //            and vertically adjacent tiles the lines they write.  This is the situation in which
 //            co-locating neighbouring tiles on one XCD pays, and it is kept to show exactly that.
+// With whole-line tiles what the order of the tiles decides is not the L2 but the memory channels:
+// all tiles of one tile row write into the same TILE*2-byte wide column stripe of `out`, and when
+// the row pitch of `out` is a power of two that stripe lives in a few channels only.  The skewed
+// raster (pid_decode.h) makes tiles that run at the same time differ in their tile row as well as
+// in their tile column; measured at 16384 x 16384 it takes the 64-wide tile from 3.9 to 5.2 TB/s
+// (the 128-wide one from 4.3 to 4.7), and it costs 1-3 % where the pitch is no power of two.
 //
 // LDS layout: row r at byte r*(TILE*2), 16-byte chunk c in slot c ^ key(r) (same idea as the
 // GEMM's B panel; TILE*2/16 slots per row).
@@ -39,7 +45,7 @@ __device__ __forceinline__ int tr_key(int row) {
 template <int TILE, int MODE>
 __global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t* __restrict__ in, uint16_t* __restrict__ out,
                                                           int M, int N, int grid_m, int grid_n, int num_xcd,
-                                                          int group_m) {
+                                                          int group_m, int skew) {
   constexpr int ROW_BYTES = TILE * 2;
   constexpr int SLOTS = ROW_BYTES / 16;                  // 16-byte chunks per tile row
   constexpr int CHUNKS = TILE * SLOTS;                   // chunks per tile
@@ -47,7 +53,7 @@ __global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t* __rest
   __shared__ __attribute__((aligned(16))) unsigned char tile[TILE * ROW_BYTES];
 
   int pm, pn;
-  swz_decode_tile((int)blockIdx.x, grid_m, grid_n, num_xcd, group_m, MODE, &pm, &pn);
+  swz_decode_tile((int)blockIdx.x, grid_m, grid_n, num_xcd, group_m, MODE | (skew ? kModeSkew : 0), &pm, &pn);
   const int m0 = pm * TILE, n0 = pn * TILE;
   const int tid = threadIdx.x;
 

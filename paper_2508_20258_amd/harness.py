@@ -41,6 +41,7 @@ import sys
 from collections import defaultdict
 
 HERE = os.path.dirname(os.path.abspath(__file__))
+MODE_NAMES = ["rr", "xcd", "xcd_groupm", "groupm", "rr_skew", "xcd_skew", "xcd_groupm_skew", "groupm_skew"]
 
 
 def _inputs(workload):
@@ -709,7 +710,7 @@ def main(argv=None):
     sub = ap.add_subparsers(dest="cmd", required=True)
     r = sub.add_parser("run")
     r.add_argument("--workload", default="cfg2_4096")
-    r.add_argument("--mode", default="xcd_groupm", choices=["rr", "xcd", "xcd_groupm", "groupm"])
+    r.add_argument("--mode", default="xcd_groupm", choices=MODE_NAMES)
     r.add_argument("--launches", type=int, default=20, help="timed launches")
     r.add_argument("--warmup-ms", type=float, default=40.0, help="GPU time of untimed launches before the timed ones")
     r.add_argument("--tile", type=int, default=0)
@@ -735,15 +736,15 @@ def main(argv=None):
     pf.set_defaults(fn=cmd_profile)
     ck = sub.add_parser("clocks")
     ck.add_argument("--workload", default="cfg2_4096")
-    ck.add_argument("--mode", default="xcd_groupm", choices=["rr", "xcd", "xcd_groupm", "groupm"])
+    ck.add_argument("--mode", default="xcd_groupm", choices=MODE_NAMES)
     ck.add_argument("--tile", type=int, default=0)
     ck.add_argument("--warmup-ms", type=float, default=40.0)
     ck.set_defaults(fn=cmd_clocks)
     t = sub.add_parser("transpose")
     t.add_argument("--m", type=int, default=16384)
     t.add_argument("--n", type=int, default=16384)
-    t.add_argument("--tile", type=int, default=128, choices=[32, 64, 128])
-    t.add_argument("--mode", default="xcd_groupm", choices=["rr", "xcd", "xcd_groupm", "groupm"])
+    t.add_argument("--tile", type=int, default=64, choices=[32, 64, 128])
+    t.add_argument("--mode", default="xcd_groupm_skew", choices=MODE_NAMES)
     t.add_argument("--launches", type=int, default=10)
     t.add_argument("--group-m", type=int, default=0)
     t.set_defaults(fn=cmd_transpose)
@@ -752,7 +753,7 @@ def main(argv=None):
     w.add_argument("--m", type=int, default=8192)
     w.add_argument("--n", type=int, default=8192)
     w.add_argument("--chunks", type=int, default=8)
-    w.add_argument("--mode", default="xcd", choices=["rr", "xcd", "xcd_groupm", "groupm"])
+    w.add_argument("--mode", default="xcd", choices=MODE_NAMES)
     w.add_argument("--launches", type=int, default=10)
     w.set_defaults(fn=cmd_rows)
     pk = sub.add_parser("peak")

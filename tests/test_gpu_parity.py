@@ -49,7 +49,7 @@ def assert_within_tolerance(c_bits, ref, what):
                                        (79, 55, 8, 4), (79, 28, 8, 4), (5, 5, 8, 4), (7, 3, 8, 4), (4, 5, 4, 4),
                                        (1, 1, 8, 4), (3, 2, 8, 9), (33, 31, 5, 3)])
 def test_device_decode_is_bit_exact_with_oracle(swz, gm, gn, X, g):
-    for mode in range(4):
+    for mode in range(8):
         tile, _ = swz.pid_map_device(gm, gn, X, g, mode)
         torch.cuda.synchronize()
         assert tile.cpu().numpy().tolist() == opm.pid_map(gm, gn, X, g, mode), (gm, gn, X, g, mode)
@@ -73,7 +73,8 @@ def test_every_xcd_really_gets_its_fair_share(swz, gm, gn):
     # counted from the XCD each workgroup reports it ran on (hardware register), not from the dispatch model
     X = swz.device_info()["num_xcd"]
     T = gm * gn
-    for mode in range(4):
+    for mode in range(8):
+        renumber, grouped, skewed = opm.mode_parts(mode)
         tile, xcc = swz.pid_map_device(gm, gn, X, 4, mode)
         torch.cuda.synchronize()
         tile, xcc = tile.cpu().numpy(), xcc.cpu().numpy()
@@ -81,10 +82,10 @@ def test_every_xcd_really_gets_its_fair_share(swz, gm, gn):
         for x in range(min(X, T)):
             mine = tile[xcc == label[x]]
             assert mine.size == T // X + (1 if x < T % X else 0), (mode, x)
-        assert opm.fair_share(tile.tolist(), gm, gn, 4, mode in (2, 3), X, mode in (1, 2))
-        if mode in (1, 2):
+        assert opm.fair_share(tile.tolist(), gm, gn, 4, grouped, X, renumber, skewed)
+        if renumber:
             # what one physical XCD computed is one unbroken stretch of the raster
-            order = opm.raster_order(gm, gn, 4, mode == 2)
+            order = opm.raster_order(gm, gn, 4, grouped, skewed)
             pos = {pm * gn + pn: l for l, (pm, pn) in enumerate(order)}
             for x in range(min(X, T)):
                 ps = sorted(pos[int(t)] for t in tile[xcc == label[x]])
@@ -127,7 +128,7 @@ def test_device_entry_point_error_paths(swz):
     t = torch.full((16,), -7, dtype=torch.int32, device="cuda")
     L = swz.lib
     assert L.swz_pid_map_device(0, 4, 8, 4, 0, t.data_ptr(), None, None) == -1
-    assert L.swz_pid_map_device(4, 4, 8, 4, 5, t.data_ptr(), None, None) == -1
+    assert L.swz_pid_map_device(4, 4, 8, 4, 8, t.data_ptr(), None, None) == -1
     assert L.swz_pid_map_device(4, 4, 8, 4, 0, None, None, None) == -1
     assert L.swz_pid_map_device(1 << 16, 1 << 15, 8, 4, 0, t.data_ptr(), None, None) == -3
     torch.cuda.synchronize()
@@ -246,6 +247,19 @@ def test_other_xcd_counts_and_group_sizes_do_not_change_the_bits(swz):
             assert np.array_equal(c, base), (X, g, mode)
 
 
+def test_skewed_modes_do_not_change_the_bits_either(swz):
+    M, N, K = 1100, 904, 160
+    a = si.matrix_bf16(23, 0, M, K, "normal")
+    b = si.matrix_bf16(23, 1, K, N, "normal")
+    for tile in (128, 256):
+        outs = run_modes(swz, a, b, modes=tuple(range(8)), bm=tile, bn=tile)
+        assert_within_tolerance(outs[0], gemm_ref.gemm(a, b), f"tile {tile}")
+        for mode in range(1, 8):
+            assert np.array_equal(outs[mode], outs[0]), (tile, mode)
+        pers = run_modes(swz, a, b, modes=(5, 6), bm=tile, bn=tile, persistent=1, num_wg=7)
+        assert np.array_equal(pers[5], outs[0]) and np.array_equal(pers[6], outs[0])
+
+
 def test_repeated_launches_are_deterministic(swz):
     a, b = si.config_inputs("cfg1_512")
     first = run_modes(swz, a, b, modes=(2,), bm=256, bn=256)[2]
@@ -323,7 +337,7 @@ def test_config5_with_128_tiles_has_a_ragged_xcd_share(swz):
 
 @pytest.mark.parametrize("gm,gn,X,g,G", [(16, 16, 8, 4, 256), (40, 28, 8, 4, 256), (5, 7, 8, 4, 6), (7, 3, 4, 2, 10), (3, 3, 8, 4, 9)])
 def test_persistent_device_decode_is_bit_exact_with_oracle(swz, gm, gn, X, g, G):
-    for mode in range(4):
+    for mode in range(8):
         tile, _ = swz.pid_map_persistent_device(gm, gn, X, g, mode, G)
         torch.cuda.synchronize()
         assert tile.cpu().numpy().tolist() == opm.pid_map_persistent(gm, gn, X, g, mode, G), (mode,)
@@ -360,12 +374,12 @@ def test_transpose_is_bit_exact_in_every_mode(swz, tile, M, N):
     x = si.matrix_bf16(600 + M, 0, M, N, "normal")
     want = transpose_ref.transpose(x)
     xd = to_dev(x)
-    for mode in range(4):
+    for mode in range(8):
         out = torch.full((N, M), float("nan"), dtype=torch.bfloat16, device="cuda")
         swz.transpose(xd, out, tile=tile, mode=mode)
         torch.cuda.synchronize()
         assert np.array_equal(to_bits(out), want), (tile, mode)
-    out = swz.transpose(xd, tile=tile, mode=2, num_xcd=3, group_m=7)
+    out = swz.transpose(xd, tile=tile, mode=6, num_xcd=3, group_m=7)
     torch.cuda.synchronize()
     assert np.array_equal(to_bits(out), want)
 
@@ -473,6 +487,20 @@ def test_harness_run_check_as_a_child_process():
     assert valid and 0 < us < 1e4, res.stdout
     res = subprocess.run(cmd[:-1] + ["--persistent", "--check"], cwd=root, capture_output=True, text=True, timeout=300)
     assert res.returncode == 0 and harness.parse_check_line(res.stdout)[0], res.stdout + res.stderr[-2000:]
+
+
+@pytest.mark.parametrize("nbytes", [16, 16 * 255, 16 * 1024, 16 * 1025, 16 * 4099, (8192 * 1024 + 77) * 16, 3 << 24])
+def test_copy_kernel_copies_every_byte_and_nothing_else(swz, nbytes):
+    g = torch.Generator(device="cuda").manual_seed(nbytes % 1000)
+    src = torch.randint(0, 256, (nbytes + 32,), dtype=torch.uint8, device="cuda", generator=g)
+    dst = torch.full((nbytes + 32,), 7, dtype=torch.uint8, device="cuda")
+    swz.copy_bytes(src[:nbytes], dst[:nbytes])
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:nbytes], src[:nbytes]) and (dst[nbytes:] == 7).all()
+    s = torch.cuda.current_stream().cuda_stream
+    assert swz.lib.swz_copy_bytes(src.data_ptr(), dst.data_ptr(), 24, s) == -2          # not a multiple of 16
+    assert swz.lib.swz_copy_bytes(src.data_ptr(), dst.data_ptr(), 0, s) == -1
+    assert swz.lib.swz_copy_bytes(None, dst.data_ptr(), 64, s) == -1
 
 
 def test_mfma_peak_kernel_runs_and_checks_its_buffer(swz):

@@ -138,7 +138,9 @@ def test_rowwise_error_paths(swz):
     assert L.swz_softmax(xp, yp, 16, 64, 0, 0, None, s) == -1          # chunks < 1
     assert L.swz_softmax(xp, yp, 16, 64, 9, 0, None, s) == -1          # more chunks than 16-byte vectors
     assert L.swz_softmax(xp, yp, 16, 60, 1, 0, None, s) == -2          # N % 8
-    assert L.swz_softmax(xp, yp, 16, 64, 1, 7, None, s) == -1          # mode
+    assert L.swz_softmax(xp, yp, 16, 64, 1, 8, None, s) == -1          # mode
+    assert L.swz_softmax(xp, yp, 16, 64, 1, 5, None, s) == -2          # skewed modes would pull a row's chunks apart: not offered
+    assert L.swz_layernorm(xp, gp, gp, yp, 16, 64, 1e-5, 1, 6, None, s) == -2
     assert L.swz_softmax(None, yp, 16, 64, 1, 0, None, s) == -1
     assert L.swz_softmax(xp + 2, yp, 16, 56, 1, 0, None, s) == -2      # alignment
     assert L.swz_softmax(xp, yp, 1 << 28, 64, 8, 0, None, s) == -3     # M * chunks

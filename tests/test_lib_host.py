@@ -29,7 +29,7 @@ def test_library_exports_every_declared_entry_point():
 GRIDS = [(gm, gn) for gm in range(1, 13) for gn in range(1, 13)]
 
 
-@pytest.mark.parametrize("mode", [0, 1, 2, 3])
+@pytest.mark.parametrize("mode", [0, 1, 2, 3, 4, 5, 6, 7])
 def test_closed_form_equals_constructive_oracle_exhaustively(mode):
     for gm, gn in GRIDS:
         for X in range(1, 13):
@@ -42,18 +42,19 @@ def test_closed_form_equals_constructive_oracle_exhaustively(mode):
                                        (79, 55, 8, 4), (79, 28, 8, 4), (5, 5, 8, 4), (7, 3, 8, 4), (4, 5, 4, 4),
                                        (128, 96, 8, 16), (65, 67, 7, 5), (1, 300, 8, 4), (300, 1, 8, 4)])
 def test_workload_grids_match_oracle_and_invariants(gm, gn, X, g):
-    for mode in range(4):
+    for mode in range(8):
         got = swz.pid_map(gm, gn, X, g, mode).tolist()
         assert got == opm.pid_map(gm, gn, X, g, mode)
-        assert opm.is_permutation(got, gm * gn) and opm.fair_share(got, gm, gn, g, mode in (2, 3), X, mode in (1, 2))
-        if mode in (1, 2):
-            assert opm.xcd_runs_contiguous(got, gm, gn, g, mode == 2, X)
+        renumber, grouped, skewed = opm.mode_parts(mode)
+        assert opm.is_permutation(got, gm * gn) and opm.fair_share(got, gm, gn, g, grouped, X, renumber, skewed)
+        if renumber:
+            assert opm.xcd_runs_contiguous(got, gm, gn, g, grouped, X, skewed)
 
 
 def test_error_paths_leave_output_untouched():
     L = swz.lib
     out = np.full(16, -7, dtype=np.int32)
-    for args in [(0, 4, 8, 4, 0), (4, 0, 8, 4, 0), (4, 4, 0, 4, 1), (4, 4, 8, 0, 2), (4, 4, 8, 4, 4), (4, 4, 8, 4, -1),
+    for args in [(0, 4, 8, 4, 0), (4, 0, 8, 4, 0), (4, 4, 0, 4, 1), (4, 4, 8, 0, 2), (4, 4, 8, 4, 8), (4, 4, 8, 4, -1),
                  (-3, 4, 8, 4, 0)]:
         assert L.swz_pid_map(*args, out.ctypes.data) == -1
         assert (out == -7).all()
@@ -99,7 +100,7 @@ def test_gemm_rejects_bad_arguments_before_touching_the_device():
     assert L.swz_gemm_ex(None, B, C, 64, 64, 64, 0, 0, ref, None) == -1
     assert L.swz_gemm_ex(A, B, None, 64, 64, 64, 0, 0, ref, None) == -1
     assert L.swz_gemm_ex(A, B, C, 0, 64, 64, 0, 0, ref, None) == -1
-    assert L.swz_gemm_ex(A, B, C, 64, 64, 64, 0, 7, ref, None) == -1
+    assert L.swz_gemm_ex(A, B, C, 64, 64, 64, 0, 8, ref, None) == -1
     assert L.swz_gemm_ex(A, B, C, 64, 64, 64, 1, 0, ref, None) == -2          # dtype
     assert L.swz_gemm_ex(A, B, C, 64, 64, 60, 0, 0, ref, None) == -2          # K % 8
     assert L.swz_gemm_ex(A, B, C, 64, 60, 64, 0, 0, ref, None) == -2          # N % 8
@@ -112,11 +113,11 @@ def test_persistent_closed_form_equals_constructive_oracle():
         for gn in range(1, 9):
             for X in (1, 3, 4, 8):
                 for G in (1, 2, 5, 8, 12, 64):
-                    for mode in range(4):
+                    for mode in range(8):
                         got = swz.pid_map_persistent(gm, gn, X, 3, mode, G).tolist()
                         assert got == opm.pid_map_persistent(gm, gn, X, 3, mode, G), (gm, gn, X, G, mode)
     for gm, gn in [(16, 16), (32, 32), (64, 8), (40, 28), (79, 55)]:
-        for mode in range(4):
+        for mode in range(8):
             assert swz.pid_map_persistent(gm, gn, 8, 4, mode, 256).tolist() == opm.pid_map_persistent(gm, gn, 8, 4, mode, 256)
 
 
@@ -125,7 +126,7 @@ def test_persistent_error_paths():
     out = np.full(64, -7, dtype=np.int32)
     assert L.swz_pid_map_persistent(4, 4, 8, 4, 0, 0, out.ctypes.data) == -1
     assert L.swz_pid_map_persistent(4, 4, 8, 4, 0, -3, out.ctypes.data) == -1
-    assert L.swz_pid_map_persistent(4, 4, 8, 4, 6, 8, out.ctypes.data) == -1
+    assert L.swz_pid_map_persistent(4, 4, 8, 4, 8, 8, out.ctypes.data) == -1
     assert L.swz_pid_map_persistent(4, 4, 8, 4, 0, 8, None) == -1
     assert (out == -7).all()
     p = swz.gemm_plan(8192, 8192, 8192, num_xcd=8, persistent=1, num_wg=256)

@@ -8,7 +8,7 @@ from oracle import pid_map as opm
 grid = st.integers(min_value=1, max_value=70)
 xcd = st.integers(min_value=1, max_value=17)
 grp = st.integers(min_value=1, max_value=80)
-mode = st.integers(min_value=0, max_value=3)
+mode = st.integers(min_value=0, max_value=7)
 
 
 @settings(max_examples=300, deadline=None)
@@ -17,9 +17,10 @@ def test_one_workgroup_per_tile(gm, gn, X, g, m):
     got = swz.pid_map(gm, gn, X, g, m)
     assert got.tolist() == opm.pid_map(gm, gn, X, g, m)
     assert np.array_equal(np.sort(got), np.arange(gm * gn))          # bijection onto [0, T)
-    assert opm.fair_share(got.tolist(), gm, gn, g, m in (2, 3), X, m in (1, 2))
-    if m in (1, 2):
-        assert opm.xcd_runs_contiguous(got.tolist(), gm, gn, g, m == 2, X)
+    renumber, grouped, skewed = opm.mode_parts(m)
+    assert opm.fair_share(got.tolist(), gm, gn, g, grouped, X, renumber, skewed)
+    if renumber:
+        assert opm.xcd_runs_contiguous(got.tolist(), gm, gn, g, grouped, X, skewed)
 
 
 @settings(max_examples=200, deadline=None)
@@ -35,7 +36,7 @@ def test_persistent(gm, gn, X, g, m, G):
 def test_large_grids_stay_bijective():
     # beyond what the oracle's lists are comfortable with: check the invariant only
     for gm, gn, X, g in [(1000, 999, 8, 4), (4096, 257, 8, 16), (3, 200000, 7, 2), (46340, 46340 // 100, 8, 4)]:
-        for m in range(4):
+        for m in range(8):
             got = swz.pid_map(gm, gn, X, g, m)
             seen = np.zeros(gm * gn, dtype=bool)
             seen[got] = True
