@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libswz.so")
 SOURCES = ["swz.hip"]
-HEADERS = ["gemm_kernel.h", "transpose_kernel.h", "rowwise_kernel.h", "mfma_peak_kernel.h", "pid_decode.h", os.path.join("..", "..", "include", "swz.h")]
+HEADERS = ["gemm_kernel.h", "aux_kernels.h", "transpose_kernel.h", "rowwise_kernel.h", "mfma_peak_kernel.h", "pid_decode.h", os.path.join("..", "..", "include", "swz.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -11,6 +11,7 @@
 #include <utility>
 
 #include "../../include/swz.h"
+#include "aux_kernels.h"
 #include "gemm_kernel.h"
 #include "mfma_peak_kernel.h"
 #include "pid_decode.h"
@@ -402,8 +403,8 @@ int swz_copy_bytes(const void* src, void* dst, int64_t bytes, hipStream_t stream
   const int64_t n = bytes / 16;
   const int64_t want = (n + 1023) / 1024;                       // a workgroup moves 1024 words per round
   const unsigned blocks = (unsigned)(want < 8192 ? want : 8192);
-  return launch(swz::copy16_kernel, dim3(blocks), dim3(256), 0, stream, static_cast<const swz::u32x4*>(src),
-                static_cast<swz::u32x4*>(dst), n);
+  return launch(swz::copy16_kernel, dim3(blocks), dim3(256), 0, stream, static_cast<const swz::aux_u32x4*>(src),
+                static_cast<swz::aux_u32x4*>(dst), n);
 }
 
 int swz_gemm_plan(int64_t M, int64_t N, int64_t K, const swz_params* params, swz_params* resolved, int* grid_m,

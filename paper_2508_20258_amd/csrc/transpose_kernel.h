@@ -64,38 +64,74 @@ __global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t* __rest
     if (q < CHUNKS) {
       const int r = q / SLOTS, c = q % SLOTS;
       t_u32x4 v = {0u, 0u, 0u, 0u};
-      if (m0 + r < M && n0 + c * 8 < N) v = *reinterpret_cast<const t_u32x4*>(in + (size_t)(m0 + r) * N + n0 + c * 8);
+      if (m0 + r < M && n0 + c * 8 < N) {
+        const t_u32x4* src = reinterpret_cast<const t_u32x4*>(in + (size_t)(m0 + r) * N + n0 + c * 8);
+        // whole-line tiles read every line exactly once: streaming loads; half-line tiles rely on the L2 keeping
+        // the line for the neighbouring tile
+        if constexpr (TILE >= 64) v = __builtin_nontemporal_load(src);
+        else v = *src;
+      }
       *reinterpret_cast<t_u32x4*>(tile + r * ROW_BYTES + ((c ^ tr_key<TILE>(r)) << 4)) = v;
     }
   }
   __syncthreads();
 
-  // ---- LDS -> out: a wave-instruction covers 16 columns (rows of out) x 32 rows of the tile ----
+  // ---- LDS -> out: a unit of work for a wave is 16 columns (rows of out) x 32 rows of the tile ----
   // lane: i = lane%16 -> column, g = lane/16 -> 8-row block; two transposing reads give rows 8g..8g+7
   const int lane = tid & 63, wave = tid >> 6;
   const int i = lane & 15, g = lane >> 4;
   constexpr int COL_BLOCKS = TILE / 16;                  // 16-column blocks
   constexpr int ROW_BLOCKS = TILE / 32;                  // 32-row blocks
   constexpr int UNITS = COL_BLOCKS * ROW_BLOCKS;         // wave-level units of work: 8 (TILE 64) or 2 (TILE 32)
-#pragma unroll
-  for (int u = wave; u < UNITS; u += 4) {
-    const int cb = u % COL_BLOCKS, rb = u / COL_BLOCKS;
+  // what a lane holds after the two transposing reads of 32-row block rb of column block cb:
+  // in[m0 + 32rb + 8g .. +7][n0 + 16cb + i]  =  out[n0 + 16cb + i][m0 + 32rb + 8g .. +7], 16 bytes
+  auto read_unit = [&](int cb, int rb) __attribute__((always_inline)) {
     const int row = 32 * rb + 8 * g + (i >> 2);          // the row whose 4 elements this lane supplies (+4 for the second read)
     const int col = 16 * cb + 4 * (i & 3);
     const unsigned char* p0 = tile + row * ROW_BYTES + (((col >> 3) ^ tr_key<TILE>(row)) << 4) + (col & 7) * 2;
     const unsigned char* p1 = tile + (row + 4) * ROW_BYTES + (((col >> 3) ^ tr_key<TILE>(row + 4)) << 4) + (col & 7) * 2;
     const t_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) t_s16x4*)p0);
     const t_s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) t_s16x4*)p1);
-    // lane now holds in[m0 + 32rb + 8g .. +7][n0 + 16cb + i]  =  out[n0 + 16cb + i][m0 + 32rb + 8g .. +7]
-    const int on = n0 + 16 * cb + i;
-    const int om = m0 + 32 * rb + 8 * g;
-    if (on < N && om < M) {                              // M % 8 == 0: the 8 elements are in or out together
-      t_u32x4 v;
-      v[0] = (uint32_t)(uint16_t)lo[0] | ((uint32_t)(uint16_t)lo[1] << 16);
-      v[1] = (uint32_t)(uint16_t)lo[2] | ((uint32_t)(uint16_t)lo[3] << 16);
-      v[2] = (uint32_t)(uint16_t)hi[0] | ((uint32_t)(uint16_t)hi[1] << 16);
-      v[3] = (uint32_t)(uint16_t)hi[2] | ((uint32_t)(uint16_t)hi[3] << 16);
-      *reinterpret_cast<t_u32x4*>(out + (size_t)on * M + om) = v;
+    t_u32x4 v;
+    v[0] = (uint32_t)(uint16_t)lo[0] | ((uint32_t)(uint16_t)lo[1] << 16);
+    v[1] = (uint32_t)(uint16_t)lo[2] | ((uint32_t)(uint16_t)lo[3] << 16);
+    v[2] = (uint32_t)(uint16_t)hi[0] | ((uint32_t)(uint16_t)hi[1] << 16);
+    v[3] = (uint32_t)(uint16_t)hi[2] | ((uint32_t)(uint16_t)hi[3] << 16);
+    return v;
+  };
+  if constexpr (ROW_BLOCKS >= 2) {
+    // Two 32-row blocks give the two 64-byte halves of 16 lines of `out`.  Lanes i and i + 8 trade one
+    // half (a rotation by 8 inside the 16-lane row), after which one store instruction writes 8 whole
+    // 128-byte lines (lanes i < 8 their left halves, lanes i >= 8 the right halves) and the next one the other 8.
+    constexpr int PAIRS = COL_BLOCKS * (ROW_BLOCKS / 2);
+#pragma unroll
+    for (int u = wave; u < PAIRS; u += 4) {
+      const int cb = u % COL_BLOCKS, rp = u / COL_BLOCKS;
+      const t_u32x4 h0 = read_unit(cb, 2 * rp), h1 = read_unit(cb, 2 * rp + 1);
+      const bool low = i < 8;
+      t_u32x4 got, s0, s1;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) got[e] = __builtin_amdgcn_mov_dpp(low ? h1[e] : h0[e], 0x128 /* row_ror:8 */, 0xf, 0xf, false);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        s0[e] = low ? h0[e] : got[e];
+        s1[e] = low ? got[e] : h1[e];
+      }
+      const int on = n0 + 16 * cb + (i & 7);
+      const int om = m0 + 64 * rp + (low ? 0 : 32) + 8 * g;
+      if (om < M) {                                        // M % 8 == 0: the 8 elements are in or out together
+        if (on < N) *reinterpret_cast<t_u32x4*>(out + (size_t)on * M + om) = s0;
+        if (on + 8 < N) *reinterpret_cast<t_u32x4*>(out + (size_t)(on + 8) * M + om) = s1;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int u = wave; u < UNITS; u += 4) {
+      const int cb = u % COL_BLOCKS, rb = u / COL_BLOCKS;
+      const t_u32x4 v = read_unit(cb, rb);
+      const int on = n0 + 16 * cb + i;
+      const int om = m0 + 32 * rb + 8 * g;
+      if (on < N && om < M) *reinterpret_cast<t_u32x4*>(out + (size_t)on * M + om) = v;
     }
   }
 }

@@ -384,27 +384,80 @@ def summarize_spans(directory, kernel_filter):
     return out
 
 
-def cmd_profile(args):
-    """Every rocprofv3 pass for the three mappings of one workload, as child processes; prints the summary table."""
-    import json
+def _rocprof(out, tag, fmt, prof_args, prog_args, limit=180):
+    """One rocprofv3 run of `python -m paper_2508_20258_amd.harness <prog_args>` into <out>/<tag> (log beside it)."""
     import shutil
     import subprocess
     env = dict(os.environ, TMPDIR=os.environ.get("TMPDIR", "/tmp"))
-    root = os.path.dirname(HERE)
+    d = os.path.join(out, tag)
+    shutil.rmtree(d, ignore_errors=True)          # a pass directory holds one run: the readers sum over every file they find
+    res = subprocess.run(["rocprofv3", *prof_args, "--output-format", fmt, "-d", d, "--", sys.executable, "-m",
+                          "paper_2508_20258_amd.harness", *prog_args],
+                         cwd=os.path.dirname(HERE), env=env, capture_output=True, text=True, timeout=limit)
+    with open(d + ".log", "w") as f:
+        f.write(res.stdout + res.stderr)
+    if res.returncode != 0:
+        sys.exit(f"rocprofv3 pass {tag} failed ({res.returncode}):\n{(res.stdout + res.stderr)[-2000:]}")
+    print(f"pass {tag} done", flush=True)
+
+
+def cmd_profile_transpose(args):
+    """rocprofv3 passes for swz_transpose over tile x mapping, as child processes; prints the summary table."""
     out = os.path.abspath(args.out)
     os.makedirs(out, exist_ok=True)
-    me = [sys.executable, "-m", "paper_2508_20258_amd.harness"]
+    m, n = args.m, args.n
+    base = ["transpose", "--m", str(m), "--n", str(n)]
+    combos = [(t, mo) for t in args.tile for mo in args.mode]
+    if not args.table_only:
+        for c, tag in (("FETCH_SIZE", "copy_fetch"), ("WRITE_SIZE", "copy_write")):
+            _rocprof(out, tag, "csv", ["--pmc", c], ["copy", "--mib", "1024", "--launches", "3"])
+        _rocprof(out, "copy_kt", "csv", ["--kernel-trace", "--stats"], ["copy", "--mib", str(4 * m * n >> 21), "--launches", str(args.launches + 1)])
+        for tile, mode in combos:
+            prog = base + ["--tile", str(tile), "--mode", mode]
+            t = f"t{tile}_{mode}"
+            _rocprof(out, t + "_kt", "csv", ["--kernel-trace", "--stats"], prog + ["--launches", str(args.launches + 1)])
+            _rocprof(out, t + "_tcc", "json", ["--pmc", "TCC_HIT", "TCC_MISS"], prog + ["--launches", "3"])
+            _rocprof(out, t + "_fetch", "csv", ["--pmc", "FETCH_SIZE"], prog + ["--launches", "3"])
+            _rocprof(out, t + "_write", "csv", ["--pmc", "WRITE_SIZE"], prog + ["--launches", "3"])
+    fs = 1024 * 1024 / _one(f"{out}/copy_fetch", "copy")["counters"]["FETCH_SIZE"]
+    ws = 1024 * 1024 / _one(f"{out}/copy_write", "copy")["counters"]["WRITE_SIZE"]
+    copy_us = _one(f"{out}/copy_kt", "copy", args.launches)["warm_avg_ns"] / 1e3
+    copy_gbs = 4.0 * m * n / (copy_us * 1e-6) / 1e9
+    H = "python3 -m paper_2508_20258_amd.harness"
+    lines = [f"rocprofv3 summary: swz transpose16_kernel, {m} x {n} 16-bit elements ({2 * m * n >> 20} MiB in, {2 * m * n >> 20} MiB out), MI355X, one GPU.",
+             "Written by (repository root, TMPDIR=/tmp):",
+             f"  {H} profile-transpose --m {m} --n {n} --out <dir>",
+             f"which runs, for TILE in {', '.join(map(str, args.tile))} and MODE in {', '.join(args.mode)}:",
+             f"  rocprofv3 --kernel-trace --stats --output-format csv -d <out> -- {H} transpose --m {m} --n {n} --tile TILE --mode MODE --launches {args.launches + 1}",
+             f"  rocprofv3 --pmc TCC_HIT TCC_MISS --output-format json -d <out> -- {H} transpose --m {m} --n {n} --tile TILE --mode MODE --launches 3",
+             "  rocprofv3 --pmc FETCH_SIZE (then WRITE_SIZE) --output-format csv -d <out> -- the same",
+             f"  and the same passes on `{H} copy` (byte-counter calibration on 1 GiB: FETCH_SIZE x {fs:.3f}, WRITE_SIZE x {ws:.3f}; kernel trace on {4 * m * n >> 20} MiB moved).",
+             f"Roofline: HBM, 8 TB/s; algorithmic bytes 4*M*N = {4 * m * n >> 20} MiB per launch.  us = kernel duration in the kernel trace, average over the last {args.launches} launches.",
+             f"The library's plain copy kernel on the same amount of data in the same session: {copy_us:.2f} us = {copy_gbs:.0f} GB/s ({100 * copy_gbs / 8000:.1f} % of 8 TB/s).",
+             "", f"{'tile':>4s} {'mode':16s} {'us':>8s} {'GB/s':>6s} {'% of 8 TB/s':>11s} {'x copy':>7s} {'L2 hit %':>8s} {'fetch MiB':>10s} {'write MiB':>10s}"]
+    for tile, mode in combos:
+        t = f"{out}/t{tile}_{mode}"
+        us = _one(t + "_kt", "transpose", args.launches)["warm_avg_ns"] / 1e3
+        gbs = 4.0 * m * n / (us * 1e-6) / 1e9
+        tj = next(iter(summarize_json(t + "_tcc", "transpose").values()))["counters"]
+        hit = 100 * tj["TCC_HIT"]["total"] / (tj["TCC_HIT"]["total"] + tj["TCC_MISS"]["total"])
+        f = _one(t + "_fetch", "transpose")["counters"]["FETCH_SIZE"] * fs / 1024
+        w = _one(t + "_write", "transpose")["counters"]["WRITE_SIZE"] * ws / 1024
+        lines.append(f"{tile:4d} {mode:16s} {us:8.2f} {gbs:6.0f} {100 * gbs / 8000:11.1f} {gbs / copy_gbs:7.2f} {hit:8.2f} {f:10.1f} {w:10.1f}")
+    text = "\n".join(lines) + "\n"
+    print(text, flush=True)
+    with open(os.path.join(out, f"transpose_{m}x{n}.txt"), "w") as f:
+        f.write(text)
 
-    def rocprof(tag, fmt, prof_args, prog_args, limit=180):
-        d = os.path.join(out, tag)
-        shutil.rmtree(d, ignore_errors=True)          # a pass directory holds one run: the readers sum over every file they find
-        res = subprocess.run(["rocprofv3", *prof_args, "--output-format", fmt, "-d", d, "--", *me, *prog_args],
-                             cwd=root, env=env, capture_output=True, text=True, timeout=limit)
-        with open(d + ".log", "w") as f:
-            f.write(res.stdout + res.stderr)
-        if res.returncode != 0:
-            sys.exit(f"rocprofv3 pass {tag} failed ({res.returncode}):\n{(res.stdout + res.stderr)[-2000:]}")
-        print(f"pass {tag} done", flush=True)
+
+def cmd_profile(args):
+    """Every rocprofv3 pass for the three mappings of one workload, as child processes; prints the summary table."""
+    import json
+    out = os.path.abspath(args.out)
+    os.makedirs(out, exist_ok=True)
+
+    def rocprof(tag, fmt, prof_args, prog_args):
+        _rocprof(out, tag, fmt, prof_args, prog_args)
 
     if not args.table_only:
         for c, tag in (("FETCH_SIZE", "copy_fetch"), ("WRITE_SIZE", "copy_write")):
@@ -734,6 +787,15 @@ def main(argv=None):
     pf.add_argument("--record", action="store_true", help="store the counters, keyed by the kernel source hash, for bench.py")
     pf.add_argument("--table-only", action="store_true", help="only rebuild the table from passes already under --out")
     pf.set_defaults(fn=cmd_profile)
+    pt = sub.add_parser("profile-transpose")
+    pt.add_argument("--m", type=int, default=16384)
+    pt.add_argument("--n", type=int, default=16384)
+    pt.add_argument("--out", required=True)
+    pt.add_argument("--tile", type=int, nargs="+", default=[64, 128, 32])
+    pt.add_argument("--mode", nargs="+", default=["rr", "xcd", "xcd_groupm", "rr_skew", "xcd_skew", "xcd_groupm_skew"], choices=MODE_NAMES)
+    pt.add_argument("--launches", type=int, default=20)
+    pt.add_argument("--table-only", action="store_true")
+    pt.set_defaults(fn=cmd_profile_transpose)
     ck = sub.add_parser("clocks")
     ck.add_argument("--workload", default="cfg2_4096")
     ck.add_argument("--mode", default="xcd_groupm", choices=MODE_NAMES)
