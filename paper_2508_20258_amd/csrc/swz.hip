@@ -180,19 +180,31 @@ int resolve_plan(int64_t M, int64_t N, int64_t K, const swz_params* p, swz_param
   return SWZ_OK;
 }
 
-template <int TILE>
-int launch_transpose(const void* in, void* out, int M, int N, int gm, int gn, int num_xcd, int group_m, int mode,
-                     hipStream_t stream) {
+constexpr int64_t kMemorySideCacheBytes = (int64_t)256 << 20;   // gfx950: 256 MB behind the L2s, in front of HBM
+
+template <int TILE, bool STREAM>
+int launch_transpose_s(const void* in, void* out, int M, int N, int gm, int gn, int num_xcd, int group_m, int mode,
+                       hipStream_t stream) {
   const dim3 grid((unsigned)(gm * gn)), block(256);
   auto* i = static_cast<const uint16_t*>(in);
   auto* o = static_cast<uint16_t*>(out);
   const int skew = swz_mode_skewed(mode) ? 1 : 0;
   switch (mode & 3) {
-    case SWZ_MODE_RR: return launch(swz::transpose16_kernel<TILE, kModeRR>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m, skew);
-    case SWZ_MODE_XCD: return launch(swz::transpose16_kernel<TILE, kModeXcd>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m, skew);
-    case SWZ_MODE_XCD_GROUPM: return launch(swz::transpose16_kernel<TILE, kModeXcdGroupM>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m, skew);
-    default: return launch(swz::transpose16_kernel<TILE, kModeGroupM>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m, skew);
+    case SWZ_MODE_RR: return launch(swz::transpose16_kernel<TILE, kModeRR, STREAM>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m, skew);
+    case SWZ_MODE_XCD: return launch(swz::transpose16_kernel<TILE, kModeXcd, STREAM>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m, skew);
+    case SWZ_MODE_XCD_GROUPM: return launch(swz::transpose16_kernel<TILE, kModeXcdGroupM, STREAM>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m, skew);
+    default: return launch(swz::transpose16_kernel<TILE, kModeGroupM, STREAM>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m, skew);
   }
+}
+
+template <int TILE>
+int launch_transpose(const void* in, void* out, int M, int N, int gm, int gn, int num_xcd, int group_m, int mode,
+                     hipStream_t stream) {
+  // streaming stores once input plus output no longer fit the memory-side cache (and only where a store
+  // instruction covers whole lines: tiles of 64 and 128)
+  if (TILE >= 64 && (int64_t)M * N * 4 > kMemorySideCacheBytes)
+    return launch_transpose_s<TILE, true>(in, out, M, N, gm, gn, num_xcd, group_m, mode, stream);
+  return launch_transpose_s<TILE, false>(in, out, M, N, gm, gn, num_xcd, group_m, mode, stream);
 }
 // How the two row-wise entry points launch: threads per row (256, or 64 = one row per wave when a
 // single workgroup per row is asked for and the row has at most 2048 elements), 16-byte vectors a

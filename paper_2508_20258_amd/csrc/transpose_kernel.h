@@ -42,7 +42,11 @@ __device__ __forceinline__ int tr_key(int row) {
   return TILE >= 64 ? (row & 3) << 1 : (row & 1) << 1;
 }
 
-template <int TILE, int MODE>
+// STREAM: the whole-line stores are streaming (non-temporal) stores.  That is the faster choice when the
+// matrices are larger than the memory-side cache (6.1 against 5.4 TB/s at 16384 x 16384 with the skewed
+// raster) and the slower one when `out` would have stayed in that cache (5.5 against 6.2 TB/s at
+// 8192 x 8192), so the host decides.
+template <int TILE, int MODE, bool STREAM>
 __global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t* __restrict__ in, uint16_t* __restrict__ out,
                                                           int M, int N, int grid_m, int grid_n, int num_xcd,
                                                           int group_m, int skew) {
@@ -120,8 +124,15 @@ __global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t* __rest
       const int on = n0 + 16 * cb + (i & 7);
       const int om = m0 + 64 * rp + (low ? 0 : 32) + 8 * g;
       if (om < M) {                                        // M % 8 == 0: the 8 elements are in or out together
-        if (on < N) *reinterpret_cast<t_u32x4*>(out + (size_t)on * M + om) = s0;
-        if (on + 8 < N) *reinterpret_cast<t_u32x4*>(out + (size_t)(on + 8) * M + om) = s1;
+        t_u32x4* d0 = reinterpret_cast<t_u32x4*>(out + (size_t)on * M + om);
+        t_u32x4* d1 = reinterpret_cast<t_u32x4*>(out + (size_t)(on + 8) * M + om);
+        if constexpr (STREAM) {
+          if (on < N) __builtin_nontemporal_store(s0, d0);
+          if (on + 8 < N) __builtin_nontemporal_store(s1, d1);
+        } else {
+          if (on < N) *d0 = s0;
+          if (on + 8 < N) *d1 = s1;
+        }
       }
     }
   } else {

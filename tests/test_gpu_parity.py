@@ -384,6 +384,22 @@ def test_transpose_is_bit_exact_in_every_mode(swz, tile, M, N):
     assert np.array_equal(to_bits(out), want)
 
 
+@pytest.mark.parametrize("tile", [64, 128])
+def test_transpose_beyond_the_memory_side_cache_is_bit_exact(swz, tile):
+    # input plus output above 256 MiB: the library switches to streaming stores; ragged in both dimensions
+    from oracle import transpose_ref
+    M, N = 8200, 8208
+    assert 4 * M * N > 256 << 20
+    x = si.matrix_bf16(800, 0, M, N, "normal")
+    want = transpose_ref.transpose(x)
+    xd = to_dev(x)
+    for mode in (0, 6):
+        out = torch.full((N, M), float("nan"), dtype=torch.bfloat16, device="cuda")
+        swz.transpose(xd, out, tile=tile, mode=mode)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_bits(out), want), (tile, mode)
+
+
 def test_transpose_error_paths(swz):
     x = to_dev(si.matrix_bf16(1, 0, 64, 64, "uniform"))
     y = torch.full((64, 64), 2.0, dtype=torch.bfloat16, device="cuda")
