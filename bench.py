@@ -63,16 +63,18 @@ def time_mode(swz, torch, a, b, c, mode, steps, warmup, **params):
     return start.elapsed_time(stop) / steps, wall_ms / steps
 
 
-def compare_mappings(swz, torch, a, b, c, variants, per_pass, warmup, flops, passes=5):
+def compare_mappings(swz, torch, a, b, c, variants, per_pass, warmup, flops, passes=9):
     """Time several mappings interleaved (passes over all of them, median per mapping) after a common
-    warm-up, so that clock ramp-up and drift do not favour whichever is measured last."""
+    warm-up, so that clock ramp-up and drift do not favour whichever is measured last; the order inside a
+    pass rotates, so that no mapping always runs right behind the same neighbour."""
     def mode_of(name):
         return swz.MODES[name.replace("persistent_", "")]
     for name, params in variants:
         time_mode(swz, torch, a, b, c, mode_of(name), warmup, warmup, **params)
     samples = {name: [] for name, _ in variants}
-    for _ in range(passes):
-        for name, params in variants:
+    for p in range(passes):
+        k = p % len(variants)
+        for name, params in variants[k:] + variants[:k]:
             ms, _ = time_mode(swz, torch, a, b, c, mode_of(name), per_pass, 2, **params)
             samples[name].append(ms)
     out = {}
