@@ -114,3 +114,20 @@ def test_transpose_oracle_pins():
     assert t.tolist() == transpose_ref.transpose_loops(x.tolist())
     assert np.array_equal(transpose_ref.transpose(t), x)                 # involution
     assert t[7, 5] == x[5, 7] and t[39, 0] == x[0, 39]
+
+
+def test_transpose_oracle_moves_four_byte_elements_verbatim():
+    # the definition does not care about the element width: every 32-bit pattern (NaN payloads, -0.0, denormals
+    # included) must arrive bit for bit at the mirrored position
+    from oracle import transpose_ref
+    rng = np.random.default_rng(11)
+    x = rng.integers(0, 1 << 32, size=(12, 20), dtype=np.uint64).astype(np.uint32)
+    x[0, 1], x[3, 2], x[5, 19] = 0x7FC00123, 0x80000000, 0x00000001
+    t = transpose_ref.transpose(x)
+    assert t.dtype == np.uint32 and t.shape == (20, 12) and t.flags["C_CONTIGUOUS"]
+    assert t.tolist() == transpose_ref.transpose_loops(x.tolist())
+    assert t[1, 0] == 0x7FC00123 and t[2, 3] == 0x80000000 and t[19, 5] == 1
+    assert np.array_equal(transpose_ref.transpose(t), x)
+    # as float32 views: same bits (a value comparison would lose the NaN)
+    f = x.view(np.float32)
+    assert np.array_equal(transpose_ref.transpose(f).view(np.uint32), t)
