@@ -149,18 +149,22 @@ int swz_gemm_ex(const void* A, const void* B, void* C, int64_t M, int64_t N, int
 int swz_gemm_plan(int64_t M, int64_t N, int64_t K, const swz_params* params, swz_params* resolved,
                   int* grid_m, int* grid_n);
 
-/* out (N x M) = transpose of in (M x N), 16-bit elements moved verbatim, both row-major and dense
+/* out (N x M) = transpose of in (M x N), elements of 2 or 4 bytes moved verbatim, both row-major and dense
  * (the paper's transpose case study, its largest win from XCD swizzling: Results; Appendix "Case
  * Study: Other Swizzling Pattern Examples").  One workgroup per tile x tile block of `in`; the tile
  * grid is ceil(M/tile) x ceil(N/tile) and hardware workgroup ids are turned into tiles exactly as
  * swz_pid_map does for that grid (`mode`, params->group_m, params->num_xcd; other fields ignored).
  *   in, out : caller-owned DEVICE pointers, 16-byte aligned, must not overlap.
+ *   elem_bytes : 2 (M and N multiples of 8) or 4 (M and N multiples of 4, tile 64 only).
  *   tile    : 64 (whole 128-byte lines; the fastest together with mode SWZ_MODE_XCD_GROUPM +
  *             SWZ_MODE_SKEW), 128 (row segments of 256 bytes) or 32 (half lines, shared between
  *             neighbouring tiles: the case where the mapping decides the L2 hit rate).
+ *   Once input plus output exceed the 256 MB memory-side cache the stores of tiles 64 and 128 are
+ *   streaming stores (the faster choice there, the slower one below it).
  * Asynchronous on `stream`; never allocates or synchronises.
- * Errors: INVALID_ARG (null, M/N < 1, unknown mode), UNSUPPORTED (elem_bytes != 2, tile not 32/64/128,
- * M or N not a multiple of 8, misaligned pointer), OVERFLOW, HIP. */
+ * Errors: INVALID_ARG (null, M/N < 1, unknown mode), UNSUPPORTED (elem_bytes not 2 or 4, tile not 32/64/128
+ * (not 64 for 4-byte elements), M or N not a multiple of 8 (4 for 4-byte elements), misaligned pointer),
+ * OVERFLOW, HIP. */
 int swz_transpose(const void* in, void* out, int64_t M, int64_t N, int elem_bytes, int tile, int mode,
                   const swz_params* params, hipStream_t stream);
 

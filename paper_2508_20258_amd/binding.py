@@ -241,17 +241,17 @@ def pid_map_persistent_device(grid_m: int, grid_n: int, num_xcd: int, group_m: i
 
 
 def transpose(x, out=None, tile: int = 64, mode: int = MODE_XCD_GROUPM + MODE_SKEW, stream=None, **params):
-    """out (N x M) = x (M x N) transposed on the GPU through swz_transpose; 16-bit element tensors.
+    """out (N x M) = x (M x N) transposed on the GPU through swz_transpose; tensors of 2-byte or 4-byte elements.
     The defaults (64-wide tiles, XCD renumbering + grouped raster + skew) are the fastest combination measured."""
     import torch
-    assert x.is_cuda and x.is_contiguous() and x.dim() == 2 and x.element_size() == 2
+    assert x.is_cuda and x.is_contiguous() and x.dim() == 2 and x.element_size() in (2, 4)
     M, N = x.shape
     if out is None:
         out = torch.empty((N, M), dtype=x.dtype, device=x.device)
     assert out.is_cuda and out.is_contiguous() and tuple(out.shape) == (N, M) and out.dtype == x.dtype
     _same_current_device(stream, x, out)
     p = _params(**params)
-    _check(lib.swz_transpose(x.data_ptr(), out.data_ptr(), M, N, 2, int(tile), int(mode), ctypes.byref(p),
+    _check(lib.swz_transpose(x.data_ptr(), out.data_ptr(), M, N, x.element_size(), int(tile), int(mode), ctypes.byref(p),
                              _stream_handle(stream)), "swz_transpose")
     return out
 

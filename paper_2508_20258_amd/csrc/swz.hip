@@ -197,6 +197,21 @@ int launch_transpose_s(const void* in, void* out, int M, int N, int gm, int gn, 
   }
 }
 
+template <bool STREAM>
+int launch_transpose32(const void* in, void* out, int M, int N, int gm, int gn, int num_xcd, int group_m, int mode,
+                       hipStream_t stream) {
+  const dim3 grid((unsigned)(gm * gn)), block(256);
+  auto* i = static_cast<const uint32_t*>(in);
+  auto* o = static_cast<uint32_t*>(out);
+  const int skew = swz_mode_skewed(mode) ? 1 : 0;
+  switch (mode & 3) {
+    case SWZ_MODE_RR: return launch(swz::transpose32_kernel<kModeRR, STREAM>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m, skew);
+    case SWZ_MODE_XCD: return launch(swz::transpose32_kernel<kModeXcd, STREAM>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m, skew);
+    case SWZ_MODE_XCD_GROUPM: return launch(swz::transpose32_kernel<kModeXcdGroupM, STREAM>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m, skew);
+    default: return launch(swz::transpose32_kernel<kModeGroupM, STREAM>, grid, block, 0, stream, i, o, M, N, gm, gn, num_xcd, group_m, skew);
+  }
+}
+
 template <int TILE>
 int launch_transpose(const void* in, void* out, int M, int N, int gm, int gn, int num_xcd, int group_m, int mode,
                      hipStream_t stream) {
@@ -348,7 +363,11 @@ int swz_transpose(const void* in, void* out, int64_t M, int64_t N, int elem_byte
   if (in == nullptr || out == nullptr || M < 1 || N < 1 || !valid_mode(mode)) return SWZ_ERR_INVALID_ARG;
   const int64_t lim = (int64_t)1 << 31;
   if (M >= lim || N >= lim) return SWZ_ERR_OVERFLOW;
-  if (elem_bytes != 2 || (tile != 32 && tile != 64 && tile != 128) || (M % 8) != 0 || (N % 8) != 0) return SWZ_ERR_UNSUPPORTED;
+  if (elem_bytes == 4) {
+    if (tile != 64 || (M % 4) != 0 || (N % 4) != 0) return SWZ_ERR_UNSUPPORTED;
+  } else if (elem_bytes != 2 || (tile != 32 && tile != 64 && tile != 128) || (M % 8) != 0 || (N % 8) != 0) {
+    return SWZ_ERR_UNSUPPORTED;
+  }
   if ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) return SWZ_ERR_UNSUPPORTED;
   int group_m = 4, num_xcd = 0;
   if (params != nullptr) {
@@ -367,6 +386,11 @@ int swz_transpose(const void* in, void* out, int64_t M, int64_t N, int elem_byte
   if (gm * gn >= lim) return SWZ_ERR_OVERFLOW;
   const int st = check_map_args((int)gm, (int)gn, num_xcd, &group_m, mode);
   if (st != SWZ_OK) return st;
+  if (elem_bytes == 4) {
+    if (M * N * 8 > kMemorySideCacheBytes)
+      return launch_transpose32<true>(in, out, (int)M, (int)N, (int)gm, (int)gn, num_xcd, group_m, mode, stream);
+    return launch_transpose32<false>(in, out, (int)M, (int)N, (int)gm, (int)gn, num_xcd, group_m, mode, stream);
+  }
   if (tile == 128) return launch_transpose<128>(in, out, (int)M, (int)N, (int)gm, (int)gn, num_xcd, group_m, mode, stream);
   return tile == 64 ? launch_transpose<64>(in, out, (int)M, (int)N, (int)gm, (int)gn, num_xcd, group_m, mode, stream)
                     : launch_transpose<32>(in, out, (int)M, (int)N, (int)gm, (int)gn, num_xcd, group_m, mode, stream);

@@ -147,4 +147,52 @@ __global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t* __rest
   }
 }
 
+// Four-byte elements: out (N x M) = in (M x N)^T, one 256-thread workgroup per 64 x 64 block (16 KiB of LDS).
+// There is no transposing LDS read for 32-bit elements, so a lane gathers its four consecutive elements of a row
+// of `out` with four 4-byte LDS reads from four consecutive tile rows.  A wave instruction covers 8 rows of
+// `out` x 32 elements = 8 whole 128-byte lines: lane l takes column 8 jb + l/8 of the tile and tile rows
+// 32 h + 4 (l%8) .. +3.  LDS layout: row r at byte r*256, 16-byte chunk c (4 columns) in slot
+// c ^ (((r >> 2) & 7) << 1): the 64 lanes of one read (8 row groups x 8 columns = 2 chunks) then hit 64
+// different banks.  Same mapping arguments, same streaming-store rule as the 16-bit kernel.
+template <int MODE, bool STREAM>
+__global__ __launch_bounds__(256) void transpose32_kernel(const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
+                                                          int M, int N, int grid_m, int grid_n, int num_xcd,
+                                                          int group_m, int skew) {
+  constexpr int TILE = 64, SLOTS = TILE / 4, CHUNKS = TILE * SLOTS, ROW_BYTES = TILE * 4;
+  __shared__ __attribute__((aligned(16))) unsigned char tile[TILE * ROW_BYTES];
+  int pm, pn;
+  swz_decode_tile((int)blockIdx.x, grid_m, grid_n, num_xcd, group_m, MODE | (skew ? kModeSkew : 0), &pm, &pn);
+  const int m0 = pm * TILE, n0 = pn * TILE;
+  const int tid = threadIdx.x;
+  auto key = [](int r) { return ((r >> 2) & 7) << 1; };
+#pragma unroll
+  for (int i = 0; i < CHUNKS / 256; ++i) {
+    const int q = tid + 256 * i;
+    const int r = q / SLOTS, c = q % SLOTS;
+    t_u32x4 v = {0u, 0u, 0u, 0u};
+    if (m0 + r < M && n0 + c * 4 < N)               // N % 4 == 0: the 4 elements are in or out together
+      v = __builtin_nontemporal_load(reinterpret_cast<const t_u32x4*>(in + (size_t)(m0 + r) * N + n0 + c * 4));
+    *reinterpret_cast<t_u32x4*>(tile + r * ROW_BYTES + ((c ^ key(r)) << 4)) = v;
+  }
+  __syncthreads();
+  const int lane = tid & 63, wave = tid >> 6;
+  const int jj = lane >> 3, rg = lane & 7;
+#pragma unroll
+  for (int u = wave; u < 16; u += 4) {                 // 8 column blocks x 2 halves of the tile's rows
+    const int jb = u >> 1, h = u & 1;
+    const int col = 8 * jb + jj;                       // tile column = row of out
+    const int row = 32 * h + 4 * rg;                   // first of this lane's 4 tile rows = column of out
+    t_u32x4 v;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      v[k] = *reinterpret_cast<const uint32_t*>(tile + (row + k) * ROW_BYTES + (((col >> 2) ^ key(row + k)) << 4) + (col & 3) * 4);
+    const int on = n0 + col, om = m0 + row;
+    if (on < N && om < M) {                            // M % 4 == 0
+      t_u32x4* dst = reinterpret_cast<t_u32x4*>(out + (size_t)on * M + om);
+      if constexpr (STREAM) __builtin_nontemporal_store(v, dst);
+      else *dst = v;
+    }
+  }
+}
+
 }  // namespace swz

@@ -569,8 +569,11 @@ def cmd_transpose(args):
 
     import paper_2508_20258_amd as swz
     torch.manual_seed(0)
-    x = torch.randint(-32768, 32767, (args.m, args.n), dtype=torch.int16, device="cuda").view(torch.bfloat16)
-    out = torch.empty((args.n, args.m), dtype=torch.bfloat16, device="cuda")
+    if args.elem_bytes == 4:
+        x = torch.randint(-(1 << 31), (1 << 31) - 1, (args.m, args.n), dtype=torch.int32, device="cuda")
+    else:
+        x = torch.randint(-32768, 32767, (args.m, args.n), dtype=torch.int16, device="cuda").view(torch.bfloat16)
+    out = torch.empty((args.n, args.m), dtype=x.dtype, device="cuda")
     mode = swz.MODES[args.mode]
     params = dict(group_m=args.group_m) if args.group_m else {}
     swz.transpose(x, out, tile=args.tile, mode=mode, **params)
@@ -582,9 +585,9 @@ def cmd_transpose(args):
     e1.record()
     torch.cuda.synchronize()
     us = e0.elapsed_time(e1) * 1e3 / max(args.launches - 1, 1)
-    gbs = 4.0 * args.m * args.n / (us * 1e-6) / 1e9
-    print(f"ran {args.launches} transposes {args.m}x{args.n} tile {args.tile} mode {args.mode} group_m {args.group_m or 4}: {us:.2f} us per launch, "
-          f"{gbs:.0f} GB/s of 4*M*N bytes ({100 * gbs / 8000:.1f} % of 8 TB/s)", flush=True)
+    gbs = 2.0 * args.elem_bytes * args.m * args.n / (us * 1e-6) / 1e9
+    print(f"ran {args.launches} transposes {args.m}x{args.n} ({args.elem_bytes}-byte elements) tile {args.tile} mode {args.mode} group_m {args.group_m or 4}: {us:.2f} us per launch, "
+          f"{gbs:.0f} GB/s of 2*M*N*elem_bytes bytes ({100 * gbs / 8000:.1f} % of 8 TB/s)", flush=True)
 
 
 def cmd_rows(args):
@@ -806,6 +809,7 @@ def main(argv=None):
     t.add_argument("--m", type=int, default=16384)
     t.add_argument("--n", type=int, default=16384)
     t.add_argument("--tile", type=int, default=64, choices=[32, 64, 128])
+    t.add_argument("--elem-bytes", type=int, default=2, choices=[2, 4])
     t.add_argument("--mode", default="xcd_groupm_skew", choices=MODE_NAMES)
     t.add_argument("--launches", type=int, default=10)
     t.add_argument("--group-m", type=int, default=0)

@@ -400,13 +400,46 @@ def test_transpose_beyond_the_memory_side_cache_is_bit_exact(swz, tile):
         assert np.array_equal(to_bits(out), want), (tile, mode)
 
 
+@pytest.mark.parametrize("M,N", [(4, 4), (64, 64), (200, 328), (1000, 76), (2048, 1028), (4100, 516)])
+def test_transpose_of_four_byte_elements_is_bit_exact_in_every_mode(swz, M, N):
+    from oracle import transpose_ref
+    rng = np.random.default_rng(M * 7 + N)
+    x = rng.integers(0, 1 << 32, size=(M, N), dtype=np.uint64).astype(np.uint32)       # every bit pattern, NaNs included
+    want = transpose_ref.transpose(x)
+    xd = torch.from_numpy(x.view(np.int32)).cuda()
+    for mode in range(8):
+        out = torch.full((N, M), -1, dtype=torch.int32, device="cuda")
+        swz.transpose(xd, out, tile=64, mode=mode)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), want), mode
+    f = xd.view(torch.float32)
+    out = swz.transpose(f, mode=6, num_xcd=3, group_m=5)
+    torch.cuda.synchronize()
+    assert out.dtype == torch.float32 and np.array_equal(out.view(torch.int32).cpu().numpy().view(np.uint32), want)
+
+
+def test_transpose_of_four_byte_elements_beyond_the_memory_side_cache(swz):
+    from oracle import transpose_ref
+    M, N = 5800, 5804                                   # 8*M*N > 256 MiB: the streaming-store instantiation; ragged
+    assert 8 * M * N > 256 << 20
+    rng = np.random.default_rng(3)
+    x = rng.integers(0, 1 << 32, size=(M, N), dtype=np.uint64).astype(np.uint32)
+    xd = torch.from_numpy(x.view(np.int32)).cuda()
+    out = torch.full((N, M), -1, dtype=torch.int32, device="cuda")
+    swz.transpose(xd, out, tile=64, mode=6)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), transpose_ref.transpose(x))
+
+
 def test_transpose_error_paths(swz):
     x = to_dev(si.matrix_bf16(1, 0, 64, 64, "uniform"))
     y = torch.full((64, 64), 2.0, dtype=torch.bfloat16, device="cuda")
     L = swz.lib
     s = torch.cuda.current_stream().cuda_stream
     assert L.swz_transpose(x.data_ptr(), y.data_ptr(), 64, 64, 2, 48, 0, None, s) == -2     # tile
-    assert L.swz_transpose(x.data_ptr(), y.data_ptr(), 64, 64, 4, 64, 0, None, s) == -2     # element size
+    assert L.swz_transpose(x.data_ptr(), y.data_ptr(), 64, 64, 8, 64, 0, None, s) == -2     # element size
+    assert L.swz_transpose(x.data_ptr(), y.data_ptr(), 32, 32, 4, 128, 0, None, s) == -2    # four-byte elements: tile 64 only
+    assert L.swz_transpose(x.data_ptr(), y.data_ptr(), 30, 32, 4, 64, 0, None, s) == -2     # M % 4
     assert L.swz_transpose(x.data_ptr(), y.data_ptr(), 60, 64, 2, 64, 0, None, s) == -2     # M % 8
     assert L.swz_transpose(x.data_ptr(), y.data_ptr(), 64, 64, 2, 64, 9, None, s) == -1     # mode
     assert L.swz_transpose(None, y.data_ptr(), 64, 64, 2, 64, 0, None, s) == -1
