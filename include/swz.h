@@ -46,7 +46,7 @@ typedef enum { SWZ_DTYPE_BF16 = 0 } swz_dtype; /* A, B, C bfloat16; accumulation
 /* Optional knobs for swz_gemm_ex / swz_gemm_plan.  A field equal to 0 means "library default". */
 typedef struct {
   int32_t bm;      /* tile rows:    128 or 256 */
-  int32_t bn;      /* tile columns: 128 or 256 (bm == bn) */
+  int32_t bn;      /* tile columns: 128 or 256 (all four combinations; one of bm, bn given: the other takes its value) */
   int32_t bk;      /* K panel per tile step: 64 (the kernel streams it as two 32-wide halves) */
   int32_t group_m; /* tile rows per band of the grouped raster (default 4) */
   int32_t num_xcd; /* XCD count assumed by the renumbering (default: detected; 8 on an unpartitioned MI355X) */
@@ -125,7 +125,9 @@ int swz_pid_map_persistent_device(int grid_m, int grid_n, int num_xcd, int group
  *   dtype   : SWZ_DTYPE_BF16.   mode : a swz_mode.
  *   Products are accumulated in fp32 in ascending-k order per tile and rounded once to
  *   bfloat16 (nearest even); the result bits do not depend on `mode`.
- *   Defaults: num_xcd detected, group_m = 4, tile 256x256x64 (128x128x64 when M <= 512 and N <= 512).
+ *   Defaults: num_xcd detected, group_m = 4, tile 256x256x64; when the 256x256 tile grid would have at
+ *   most half as many tiles as the device has compute units, 128x256x64, and at most a quarter, 128x128x64
+ *   (the chip is then better filled by more and smaller tiles; the result bits do not depend on the tile shape).
  * Asynchronous on `stream`; never allocates or synchronises.
  * Errors: INVALID_ARG (null pointer, M/N/K < 1, unknown mode), UNSUPPORTED (other dtype,
  * K or N not a multiple of 8, misaligned pointer), OVERFLOW (tile count >= 2^31 or a
@@ -136,7 +138,7 @@ int swz_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_
 /* swz_gemm (paper: Appendix "Case Study: GEMM Swizzling") with explicit tile shape / group_m /
  * num_xcd / launch style (null params = all defaults); persistent = 1 is the launch style of the
  * paper's own listing (as many workgroups as compute units, each looping over tiles).
- * UNSUPPORTED for a tile shape other than 128x128x64 or 256x256x64.  The persistent launch computes
+ * UNSUPPORTED for tile rows or columns other than 128 or 256, or bk other than 64.  The persistent launch computes
  * every tile with the same instruction sequence, so its C is bit-identical to the default launch. */
 int swz_gemm_ex(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,
                 const swz_params* params, hipStream_t stream);

@@ -115,7 +115,6 @@ struct GemmShape {
   static constexpr int LDS_BYTES = RING_BYTES;
   static_assert(BM % (WM * 16) == 0 && BN % (WN * 16) == 0, "wave tiling");
   static_assert((BM * 8) % NT == 0 && (kStepK * B_ROW_CHUNKS) % NT == 0 && A_LOADS % 2 == 0, "load tiling");
-  static_assert(A_LOADS / 2 == B_LOADS, "A and B loads alternate within a step");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS per workgroup");
 };
 

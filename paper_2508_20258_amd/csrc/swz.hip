@@ -29,7 +29,7 @@ struct DeviceFacts {
   int num_xcd = 0, cus = 0, l2_bytes = 0, lds_bytes = 0;   // num_xcd 0: could not be derived
 };
 DeviceFacts g_facts[kMaxDevices];
-std::atomic<bool> g_attr_set[kMaxDevices][2][4][2];
+std::atomic<bool> g_attr_set[kMaxDevices][4][4][2];
 std::mutex g_mu;
 
 // SWZ_NUM_XCD in the environment (read once per process): the XCD count to assume instead of the
@@ -156,12 +156,25 @@ int resolve_plan(int64_t M, int64_t N, int64_t K, const swz_params* p, swz_param
   if (q.bm < 0 || q.bn < 0 || q.bk < 0 || q.group_m < 0 || q.num_xcd < 0 || q.num_wg < 0 ||
       (q.persistent != 0 && q.persistent != 1))
     return SWZ_ERR_INVALID_ARG;
-  if (q.bm == 0 && q.bn == 0) q.bm = q.bn = (M <= 512 && N <= 512) ? 128 : 256;
+  if (q.bm == 0 && q.bn == 0) {
+    // 256x256 tiles are the faster kernel once they fill the chip; below that, more and smaller tiles are.
+    // Measured (tiles of the 256x256 grid against compute units): up to a quarter, 128x128 tiles are 1.6-2.0x
+    // faster; between a quarter and a half, 128x256 tiles are 1.25-1.3x faster (and 3-14 % ahead of 128x128);
+    // above a half, 256x256 tiles win by 1.2-1.3x.  The device is only asked where its CU count decides.
+    const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
+    int cus = 256;                                  // assumed where no device can be asked (a whole MI355X)
+    if (t256 > 8 && t256 <= 152) {
+      DeviceFacts f;
+      if (query_device(&f) == SWZ_OK && f.cus > 0) cus = f.cus;
+    }
+    q.bm = 2 * t256 <= cus ? 128 : 256;
+    q.bn = 4 * t256 <= cus ? 128 : 256;
+  }
   if (q.bm == 0) q.bm = q.bn;
   if (q.bn == 0) q.bn = q.bm;
   if (q.bk == 0) q.bk = kDefaultBK;
   if (q.group_m == 0) q.group_m = 4;
-  if (!((q.bm == 128 && q.bn == 128) || (q.bm == 256 && q.bn == 256)) || q.bk != kDefaultBK) return SWZ_ERR_UNSUPPORTED;
+  if (!((q.bm == 128 || q.bm == 256) && (q.bn == 128 || q.bn == 256)) || q.bk != kDefaultBK) return SWZ_ERR_UNSUPPORTED;
   const int64_t gm = (M + q.bm - 1) / q.bm, gn = (N + q.bn - 1) / q.bn;
   if (gm * gn >= lim) return SWZ_ERR_OVERFLOW;
   if (q.num_xcd == 0 || (q.persistent && q.num_wg == 0)) {
@@ -448,6 +461,12 @@ int swz_gemm_plan(int64_t M, int64_t N, int64_t K, const swz_params* params, swz
   return resolve_plan(M, N, K, params, resolved, grid_m, grid_n);
 }
 
+// The four tile shapes: 8 waves each; 256x256 -> wave tile 128x64, the other three -> wave tile 64x64 or 64x32.
+using Shape128 = swz::GemmShape<128, 128, 2, 4>;
+using Shape256 = swz::GemmShape<256, 256, 2, 4>;
+using Shape128x256 = swz::GemmShape<128, 256, 2, 4>;
+using Shape256x128 = swz::GemmShape<256, 128, 4, 2>;
+
 // Checks shared by the GEMM entry points; on success r, grid_m, grid_n and group_m describe the launch.
 static int check_gemm(const void* A, const void* B, const void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,
                       const swz_params* params, swz_params* r, int* grid_m, int* grid_n, int* group_m) {
@@ -470,11 +489,13 @@ int swz_gemm_ex(const void* A, const void* B, void* C, int64_t M, int64_t N, int
   int grid_m = 0, grid_n = 0, group_m = 0;
   const int st = check_gemm(A, B, C, M, N, K, dtype, mode, params, &r, &grid_m, &grid_n, &group_m);
   if (st != SWZ_OK) return st;
+  if (r.bm == 128 && r.bn == 128)
+    return launch_gemm<Shape128>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd, group_m, mode, r.num_wg, stream, 0);
   if (r.bm == 128)
-    return launch_gemm<swz::GemmShape<128, 128, 2, 4>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
-                                                               group_m, mode, r.num_wg, stream, 0);
-  return launch_gemm<swz::GemmShape<256, 256, 2, 4>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
-                                                             group_m, mode, r.num_wg, stream, 1);
+    return launch_gemm<Shape128x256>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd, group_m, mode, r.num_wg, stream, 2);
+  if (r.bn == 128)
+    return launch_gemm<Shape256x128>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd, group_m, mode, r.num_wg, stream, 3);
+  return launch_gemm<Shape256>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd, group_m, mode, r.num_wg, stream, 1);
 }
 
 int swz_gemm_probe(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,
@@ -487,11 +508,13 @@ int swz_gemm_probe(const void* A, const void* B, void* C, int64_t M, int64_t N, 
   if (r.persistent) return SWZ_ERR_UNSUPPORTED;
   if (probe_words < (int64_t)grid_m * grid_n * swz::kProbeWords) return SWZ_ERR_INVALID_ARG;
   if (reinterpret_cast<uintptr_t>(probe) & 7) return SWZ_ERR_UNSUPPORTED;
+  if (r.bm == 128 && r.bn == 128)
+    return launch_gemm_probe<Shape128>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd, group_m, mode, probe, stream);
   if (r.bm == 128)
-    return launch_gemm_probe<swz::GemmShape<128, 128, 2, 4>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
-                                                                     group_m, mode, probe, stream);
-  return launch_gemm_probe<swz::GemmShape<256, 256, 2, 4>>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd,
-                                                                   group_m, mode, probe, stream);
+    return launch_gemm_probe<Shape128x256>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd, group_m, mode, probe, stream);
+  if (r.bn == 128)
+    return launch_gemm_probe<Shape256x128>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd, group_m, mode, probe, stream);
+  return launch_gemm_probe<Shape256>(A, B, C, (int)M, (int)N, (int)K, grid_m, grid_n, r.num_xcd, group_m, mode, probe, stream);
 }
 
 int swz_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int dtype, int mode,

@@ -234,6 +234,18 @@ def test_all_ones_gives_k(swz):
     assert (si.bf16_bits_to_f64(outs[2]) == float(K)).all()
 
 
+def test_default_tile_follows_how_well_the_grid_fills_the_device(swz):
+    cus = swz.device_info()["compute_units"]
+    for M, N, K in [(512, 512, 512), (2048, 2048, 2048), (2560, 2560, 64), (3072, 3072, 64), (4096, 4096, 64), (8192, 1024, 64),
+                    (300, 40000, 64), (10000, 7000, 64)]:
+        t256 = -(-M // 256) * -(-N // 256)
+        want = (128, 128) if 4 * t256 <= cus else (128, 256) if 2 * t256 <= cus else (256, 256)
+        plan = swz.gemm_plan(M, N, K)
+        assert (plan["bm"], plan["bn"]) == want, (M, N, t256, plan)
+    # an explicit tile is never overridden
+    assert swz.gemm_plan(2048, 2048, 2048, bm=256, bn=256)["bm"] == 256 and swz.gemm_plan(8192, 8192, 64, bm=128, bn=128)["bm"] == 128
+
+
 def test_other_xcd_counts_and_group_sizes_do_not_change_the_bits(swz):
     M, N, K = 1100, 904, 128
     a = si.matrix_bf16(21, 0, M, K, "normal")
@@ -455,6 +467,24 @@ def test_tile_shape_does_not_change_the_bits(swz, M, N, K):
     big = run_modes(swz, a, b, modes=(2,), bm=256, bn=256)[2]
     small = run_modes(swz, a, b, modes=(0,), bm=128, bn=128)[0]
     assert np.array_equal(big, small)
+
+
+@pytest.mark.parametrize("bm,bn", [(128, 256), (256, 128)])
+@pytest.mark.parametrize("M,N,K", [(1300, 1096, 200), (129, 264, 72), (2100, 2064, 544), (257, 8, 1000), (640, 776, 32)])
+def test_rectangular_tiles_give_the_same_bits_in_every_mode_and_launch_style(swz, bm, bn, M, N, K):
+    a = si.matrix_bf16(950 + M, 0, M, K, "normal")
+    b = si.matrix_bf16(950 + M, 1, K, N, "uniform")
+    base = run_modes(swz, a, b, modes=(0,), bm=256, bn=256)[0]
+    assert_within_tolerance(base, gemm_ref.gemm(a, b), "256x256 tiles")
+    outs = run_modes(swz, a, b, modes=(0, 1, 2, 3, 6), bm=bm, bn=bn)
+    for mode, c in outs.items():
+        assert np.array_equal(c, base), (bm, bn, mode)
+    pers = run_modes(swz, a, b, modes=(2, 3), bm=bm, bn=bn, persistent=1, num_wg=5)
+    assert np.array_equal(pers[2], base) and np.array_equal(pers[3], base)
+    c = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    swz.gemm_probe(to_dev(a), to_dev(b), c, mode=2, bm=bm, bn=bn)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(c), base)
 
 
 def _random_shapes():

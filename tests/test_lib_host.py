@@ -78,9 +78,15 @@ def test_plan_resolves_tiles_without_a_device_when_num_xcd_is_given():
     assert (p["bm"], p["bn"], p["bk"], p["grid_m"], p["grid_n"], p["group_m"]) == (128, 128, 64, 4, 4, 4)
     p = swz.gemm_plan(10000, 7000, 4096, num_xcd=8)
     assert (p["bm"], p["grid_m"], p["grid_n"]) == (256, 40, 28)
+    # grids far from the device's CU count are decided without asking a device: tiny -> 128-wide, huge -> 256-wide
+    assert swz.gemm_plan(1024, 1024, 64, num_xcd=8)["bm"] == 128 and swz.gemm_plan(8192, 8192, 64, num_xcd=8)["bm"] == 256
+    p = swz.gemm_plan(10000, 7000, 4096, num_xcd=8, bm=128, bn=256)
+    assert (p["bm"], p["bn"], p["grid_m"], p["grid_n"]) == (128, 256, 79, 28)
+    p = swz.gemm_plan(10000, 7000, 4096, num_xcd=8, bm=256, bn=128)
+    assert (p["grid_m"], p["grid_n"]) == (40, 55)
     p = swz.gemm_plan(10000, 7000, 4096, num_xcd=8, bm=128, bn=128)
     assert (p["grid_m"], p["grid_n"]) == (79, 55)
-    for bad in [dict(bm=64, bn=64), dict(bm=256, bn=128), dict(bk=32)]:
+    for bad in [dict(bm=64, bn=64), dict(bm=256, bn=64), dict(bm=512, bn=256), dict(bk=32)]:
         with pytest.raises(swz.SwzError) as e:
             swz.gemm_plan(1024, 1024, 1024, num_xcd=8, **bad)
         assert e.value.status == -2
