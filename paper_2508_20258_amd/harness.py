@@ -450,6 +450,60 @@ def cmd_profile_transpose(args):
         f.write(text)
 
 
+ROW_CASES = [  # (M, N, chunks, mode): chunked rows under both dispatch orders, one workgroup per row, one wave per row, beyond the cache
+    (1024, 65536, 8, "rr"), (1024, 65536, 8, "xcd"), (1024, 65536, 1, "rr"), (8192, 8192, 8, "rr"), (8192, 8192, 8, "xcd"),
+    (8192, 8192, 1, "rr"), (65536, 1024, 1, "rr"), (32768, 16384, 1, "rr")]
+
+
+def cmd_profile_rows(args):
+    """rocprofv3 passes for swz_softmax / swz_layernorm over ROW_CASES, as child processes; prints the summary table."""
+    out = os.path.abspath(args.out)
+    os.makedirs(out, exist_ok=True)
+    cases = [(op, m, n, c, mode) for op in ("softmax", "layernorm") for (m, n, c, mode) in ROW_CASES]
+    if not args.table_only:
+        for c, tag in (("FETCH_SIZE", "copy_fetch"), ("WRITE_SIZE", "copy_write")):
+            _rocprof(out, tag, "csv", ["--pmc", c], ["copy", "--mib", "1024", "--launches", "3"])
+        _rocprof(out, "copy_kt", "csv", ["--kernel-trace", "--stats"], ["copy", "--mib", "1024", "--launches", str(args.launches + 1)])
+        for op, m, n, c, mode in cases:
+            prog = ["rows", "--op", op, "--m", str(m), "--n", str(n), "--chunks", str(c), "--mode", mode]
+            t = f"{op}_{m}x{n}_c{c}_{mode}"
+            _rocprof(out, t + "_kt", "csv", ["--kernel-trace", "--stats"], prog + ["--launches", str(args.launches + 1)])
+            _rocprof(out, t + "_tcc", "json", ["--pmc", "TCC_HIT", "TCC_MISS"], prog + ["--launches", "3"])
+            _rocprof(out, t + "_fetch", "csv", ["--pmc", "FETCH_SIZE"], prog + ["--launches", "3"])
+            _rocprof(out, t + "_write", "csv", ["--pmc", "WRITE_SIZE"], prog + ["--launches", "3"])
+    fs = 1024 * 1024 / _one(f"{out}/copy_fetch", "copy")["counters"]["FETCH_SIZE"]
+    ws = 1024 * 1024 / _one(f"{out}/copy_write", "copy")["counters"]["WRITE_SIZE"]
+    copy_us = _one(f"{out}/copy_kt", "copy", args.launches)["warm_avg_ns"] / 1e3
+    copy_gbs = 2.0 * (1 << 30) / (copy_us * 1e-6) / 1e9
+    H = "python3 -m paper_2508_20258_amd.harness"
+    lines = ["rocprofv3 summary: swz softmax_rows_kernel / layernorm_rows_kernel, bf16, MI355X, one GPU.",
+             "Written by (repository root, TMPDIR=/tmp):",
+             f"  {H} profile-rows --out <dir>",
+             "which runs, for OP in softmax, layernorm and (M, N, CHUNKS, MODE) as in the table:",
+             f"  rocprofv3 --kernel-trace --stats --output-format csv -d <out> -- {H} rows --op OP --m M --n N --chunks CHUNKS --mode MODE --launches {args.launches + 1}",
+             f"  rocprofv3 --pmc TCC_HIT TCC_MISS --output-format json -d <out> -- {H} rows --op OP --m M --n N --chunks CHUNKS --mode MODE --launches 3",
+             "  rocprofv3 --pmc FETCH_SIZE (then WRITE_SIZE) --output-format csv -d <out> -- the same",
+             f"  and the same passes on `{H} copy --mib 1024` (byte-counter calibration: FETCH_SIZE x {fs:.3f}, WRITE_SIZE x {ws:.3f}).",
+             "Roofline: HBM, 8 TB/s; algorithmic bytes 4*M*N per launch (read x once, write y once): 256 MiB, 2 GiB for 32768 x 16384.",
+             "Launches repeat over the same data; 256 MiB is partly held by the 256 MB memory-side cache between launches, 2 GiB is not.",
+             f"The library's plain copy kernel, 1 GiB in + 1 GiB out, same session: {copy_us:.2f} us = {copy_gbs:.0f} GB/s ({100 * copy_gbs / 8000:.1f} % of 8 TB/s).",
+             f"us = kernel duration in the kernel trace, average over the last {args.launches} launches.  chunks = workgroups per row; each reads the whole row.",
+             "", f"{'op':9s} {'M x N':>14s} {'chunks':>6s} {'mode':5s} {'us':>8s} {'GB/s':>6s} {'% of 8 TB/s':>11s} {'L2 hit %':>8s} {'fetch MiB':>10s} {'write MiB':>10s}"]
+    for op, m, n, c, mode in cases:
+        t = f"{out}/{op}_{m}x{n}_c{c}_{mode}"
+        us = _one(t + "_kt", "rows_kernel", args.launches)["warm_avg_ns"] / 1e3
+        gbs = 4.0 * m * n / (us * 1e-6) / 1e9
+        tj = next(iter(summarize_json(t + "_tcc", "rows_kernel").values()))["counters"]
+        hit = 100 * tj["TCC_HIT"]["total"] / (tj["TCC_HIT"]["total"] + tj["TCC_MISS"]["total"])
+        f = _one(t + "_fetch", "rows_kernel")["counters"]["FETCH_SIZE"] * fs / 1024
+        w = _one(t + "_write", "rows_kernel")["counters"]["WRITE_SIZE"] * ws / 1024
+        lines.append(f"{op:9s} {m:>6d} x {n:<6d} {c:6d} {mode:5s} {us:8.2f} {gbs:6.0f} {100 * gbs / 8000:11.1f} {hit:8.2f} {f:10.1f} {w:10.1f}")
+    text = "\n".join(lines) + "\n"
+    print(text, flush=True)
+    with open(os.path.join(out, "rowwise_softmax_layernorm.txt"), "w") as f:
+        f.write(text)
+
+
 def cmd_profile(args):
     """Every rocprofv3 pass for the three mappings of one workload, as child processes; prints the summary table."""
     import json
@@ -799,6 +853,11 @@ def main(argv=None):
     pt.add_argument("--launches", type=int, default=20)
     pt.add_argument("--table-only", action="store_true")
     pt.set_defaults(fn=cmd_profile_transpose)
+    pr = sub.add_parser("profile-rows")
+    pr.add_argument("--out", required=True)
+    pr.add_argument("--launches", type=int, default=10)
+    pr.add_argument("--table-only", action="store_true")
+    pr.set_defaults(fn=cmd_profile_rows)
     ck = sub.add_parser("clocks")
     ck.add_argument("--workload", default="cfg2_4096")
     ck.add_argument("--mode", default="xcd_groupm", choices=MODE_NAMES)
