@@ -165,3 +165,50 @@ def test_clocks_report_on_hand_made_stamps():
     assert float(x1[2]) == 1100.0 and abs(float(x1[5]) - 1500) <= 2
     assert float(x1[9]) > float(x0[9])                     # the slower XCD's loop lasts longer
     assert "slowest XCD 15" in lines[-1] and "fastest 20" in lines[-1]
+
+
+def test_profile_table_from_canned_rocprof_output(tmp_path):
+    # the table kept under profiles/ and the record bench.py reports, rebuilt from hand-made pass directories:
+    # scaling of the byte counters by the copy calibration, hit rates total and per XCD, MfmaUtil, last-N kernel time
+    def counters_csv(d, kernel, rows):
+        os.makedirs(d)
+        (d / "1_counter_collection.csv").write_text('"Dispatch_Id","Kernel_Name","Counter_Name","Counter_Value"\n' +
+                                                    "".join(f'{i},"{kernel}","{c}",{v}\n' for i, c, v in rows))
+
+    src = tmp_path / "prof"
+    counters_csv(src / "copy_fetch", "copy16_kernel", [(1, "FETCH_SIZE", 524288.0)])      # reads half the KiB copied -> x2
+    counters_csv(src / "copy_write", "copy16_kernel", [(1, "WRITE_SIZE", 1048576.0)])     # -> x1
+    inst = [{"dimensions": [{"dimension_name": "DIMENSION_XCC", "index": x}]} for x in range(8)]
+    for mode, (hit, miss) in {"rr": (70, 30), "xcd": (70, 30), "xcd_groupm": (80, 20)}.items():
+        t = src / f"cfg1_512_{mode}"
+        kt = tmp_path / "prof" / f"cfg1_512_{mode}_kt"
+        os.makedirs(kt)
+        rows = "".join(f'"KERNEL_DISPATCH","gemm_bf16_kernel<{mode}>",{1000 * i},{1000 * i + (900 if i < 30 else 500)}\n' for i in range(40))
+        (kt / "1_kernel_trace.csv").write_text('"Kind","Kernel_Name","Start_Timestamp","End_Timestamp"\n' + rows)
+        (tmp_path / "prof" / f"cfg1_512_{mode}_kt.log").write_text("ran 30 warm-up + 10 timed launches of cfg1_512 mode x: 0.61 us per launch\n")
+        tcc = tmp_path / "prof" / f"cfg1_512_{mode}_tcc"
+        os.makedirs(tcc)
+        doc = {"rocprofiler-sdk-tool": [{
+            "counters": [{"id": {"handle": 1}, "name": "TCC_HIT", "instances": inst}, {"id": {"handle": 2}, "name": "TCC_MISS", "instances": inst}],
+            "kernel_symbols": [{"kernel_id": 5, "formatted_kernel_name": "gemm_bf16_kernel"}],
+            "callback_records": {"counter_collection": [{"dispatch_data": {"dispatch_info": {"kernel_id": 5}},
+                                                        "records": [{"counter_id": {"handle": 1}, "value": hit + x} for x in range(8)]
+                                                        + [{"counter_id": {"handle": 2}, "value": miss - x} for x in range(8)]}]}}]}
+        (tcc / "1_results.json").write_text(json.dumps(doc))
+        counters_csv(tmp_path / "prof" / f"cfg1_512_{mode}_fetch", "gemm_bf16_kernel", [(1, "FETCH_SIZE", 1536.0)])
+        counters_csv(tmp_path / "prof" / f"cfg1_512_{mode}_write", "gemm_bf16_kernel", [(1, "WRITE_SIZE", 512.0)])
+        counters_csv(tmp_path / "prof" / f"cfg1_512_{mode}_sq", "gemm_bf16_kernel",
+                     [(1, "SQ_VALU_MFMA_BUSY_CYCLES", 512000.0), (1, "GRBM_GUI_ACTIVE", 8000.0), (1, "SQ_INSTS_VALU_MFMA_MOPS_BF16", 524288.0),
+                      (1, "SQ_LDS_BANK_CONFLICT", 0.0), (1, "SQ_LDS_IDX_ACTIVE", 100.0), (1, "SQ_BUSY_CU_CYCLES", 1.0), (1, "SQ_WAVE_CYCLES", 1.0)])
+    text, record = harness.profile_table(str(src), "cfg1_512", 40.0, 10)
+    r = record["xcd_groupm"]
+    assert r["kernel_us"] == 0.5                                             # the last 10 dispatches, not the 30 slower ones before
+    assert abs(r["l2_hit_pct"] - 100 * (8 * 80 + 28) / 800) < 1e-9           # sum over the instances
+    assert abs(r["l2_hit_pct_per_xcd"][3] - 83.0) < 1e-9 and len(r["l2_hit_pct_per_xcd"]) == 8
+    assert r["fetch_bytes"] == 1536 * 2 * 1024 and r["write_bytes"] == 512 * 1024   # scaled by the copy calibration
+    assert abs(r["mfma_util_pct"] - 100 * 512000 / (8000 / 8 * 1024)) < 1e-9
+    assert r["mfma_flop_issued"] == 524288 * 512 == 2 * 512 ** 3
+    assert abs(record["rr"]["model_hit_pct"] - 25.0) < 1e-9                  # 4 x 4 grid, two tiles per XCD: nothing shared beyond 2 of 8 requests
+    line = next(l for l in text.splitlines() if l.startswith("xcd_groupm"))
+    assert line.split()[1] == "0.50" and line.split()[2] == "0.90" and line.split()[4] == "0.61"
+    assert "scale FETCH_SIZE by 2.000, WRITE_SIZE by 1.000" in text
