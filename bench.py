@@ -207,6 +207,8 @@ def main():
         return 100.0 * t / PEAK_BF16_TFLOPS
 
     variants = [("rr", {}), ("xcd", {}), ("xcd_groupm", {}),
+                # grouped raster without the XCD renumbering: what a kernel unaware of the chiplets would use
+                ("groupm", {}),
                 # the paper's own launch style (as many workgroups as compute units, tile loop)
                 ("persistent_rr", dict(persistent=1)), ("persistent_xcd_groupm", dict(persistent=1))]
     per_mode = compare_mappings(swz, torch, a, b, c, variants, PER_PASS, max(args.warmup, PER_PASS), flops)
