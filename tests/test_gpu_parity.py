@@ -329,6 +329,34 @@ def test_full_size_workloads_sampled_against_oracle_and_bit_identical_across_mod
     assert not np.isnan(si.bf16_bits_to_f64(c)).any()   # every element of C was written
 
 
+def test_a_larger_than_four_gibibytes_is_addressed_correctly(swz):
+    # 70000 x 32768 bf16 = 4.27 GiB: tile bases beyond 2^32 bytes.  A is a seeded 2048-row block repeated down the
+    # matrix (row i = block row i mod 2048), so the oracle can form any row without a host copy of the whole of A.
+    M, N, K, R = 70000, 264, 32768, 2048
+    block = si.matrix_bf16(12, 0, R, K, "normal", 1.0 / np.sqrt(K))
+    b = si.matrix_bf16(12, 1, K, N, "normal")
+    a_dev = to_dev(block).repeat(-(-M // R), 1)[:M].contiguous()
+    assert a_dev.numel() * 2 > 1 << 32
+    b_dev = to_dev(b)
+    rng = np.random.default_rng(12)
+    ii = np.concatenate([rng.integers(0, M, 600), [0, 255, 256, 65535, 65536, 65537, 69887, 69888, M - 1]])   # around the 4 GiB row too
+    jj = np.concatenate([rng.integers(0, N, 600), [0, 1, 255, 256, 263, 7, 8, 262, N - 1]])
+    ref = gemm_ref.gemm_elems(block, b, ii % R, jj)
+    outs = {}
+    for mode, params in ((0, {}), (2, {}), (2, dict(persistent=1))):
+        c = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        swz.gemm(a_dev, b_dev, c, mode=mode, bm=256, bn=256, **params)
+        torch.cuda.synchronize()
+        outs[(mode, bool(params))] = c
+        got = to_bits(c[torch.from_numpy(ii).cuda(), torch.from_numpy(jj).cuda()])
+        assert_within_tolerance(got, ref, f"mode {mode} {params}")
+        assert not torch.isnan(c).any()
+    base = outs[(0, False)].view(torch.int16)
+    assert torch.equal(outs[(2, False)].view(torch.int16), base) and torch.equal(outs[(2, True)].view(torch.int16), base)
+    # rows that repeat the same block row must be bit-identical wherever they sit in memory
+    assert torch.equal(base[:R], base[32 * R:33 * R]) and torch.equal(base[100:1000], base[100 + 33 * R:1000 + 33 * R])
+
+
 def test_config5_with_128_tiles_has_a_ragged_xcd_share(swz):
     # 79 x 55 = 4345 tiles = 8*543 + 1: XCD 0 gets one workgroup more than the others
     cfg = si.CONFIGS["cfg5_ragged"]
